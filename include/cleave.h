@@ -1,0 +1,160 @@
+/*
+ * cleave.h -- C ABI of the MI355X sub-GEMM task library.
+ *
+ * The library implements the compute path of Cleave's parameter-server
+ * training scheme on one GPU:
+ *
+ *   plan     Task generation (paper Sec. 3.2 "Seamless training"; Sec. 4.1
+ *            "Search space of GEMM"): a GEMM  O = op(A) . op(B)  with
+ *            op(A) of size M x K and op(B) of size K x N is cut into row
+ *            blocks of A and column blocks of B; one task is one (row block,
+ *            column block) pair and produces the matching block of O.  The
+ *            blocks cover O exactly once, without redundant work (Sec. 4.1,
+ *            coverage constraint) and no task is empty (Sec. 4.1, zero-task
+ *            constraint).  In addition the inner dimension is cut into S
+ *            contiguous chunks ("K-split"), so a task is (tile, chunk) and
+ *            yields a partial block; S = 1 is the paper's own case.
+ *   execute  Sub-GEMM execution (Sec. 4.1, computation-cost term: a task
+ *            costs 2 * m_len * n_len * k_len flops): every task reads its
+ *            rows of op(A) and columns of op(B) and stores an fp32 partial
+ *            block.  Re-executing a task (Sec. 4.2 churn recovery: lost
+ *            shards are issued again) gives bitwise identical output.
+ *   reduce   Parameter-server aggregation (Sec. 3.2: the PS aggregates the
+ *            computed outputs): the S partial blocks of every tile are summed
+ *            in ascending chunk order, ((P0 + P1) + P2) + ..., in fp32, and
+ *            written into the full output C.
+ *
+ * Conventions
+ *   - Every function returns CLEAVE_OK (0) or a negative cleave_status; no
+ *     exception or abort crosses this boundary.  On error, output arguments
+ *     are left untouched.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory of the current device, owned by the caller.  The library
+ *     never allocates, frees or retains A, B, partials or C.
+ *   - Matrices are row-major with a leading dimension in elements.
+ *       transA = 0: A is stored M x K (lda >= K); transA = 1: A is stored
+ *       K x M (lda >= M) and read as its transpose, without a copy.
+ *       transB = 0: B is stored K x N (ldb >= N); transB = 1: B is stored
+ *       N x K (ldb >= K).  (Forward X.W is (0,0); dX = dY.W^T is (0,1);
+ *       dW = X^T.dY is (1,0).)
+ *   - execute and reduce enqueue work on the given HIP stream (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return without waiting
+ *     for it.  The first execute/reduce of a plan on a device uploads the
+ *     plan's tables with a blocking copy; cleave_plan_upload does that ahead
+ *     of time.
+ */
+#ifndef CLEAVE_H
+#define CLEAVE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CLEAVE_OK = 0,
+  CLEAVE_EINVAL = -1, /* bad size, edge list, split count, pointer, leading dimension, enum */
+  CLEAVE_ENOMEM = -2, /* host or device allocation of plan tables failed */
+  CLEAVE_EHIP = -3    /* a HIP runtime call failed; see cleave_last_hip_error */
+} cleave_status;
+
+typedef enum { CLEAVE_F32 = 0, CLEAVE_BF16 = 1 } cleave_dtype;
+
+/* One sub-GEMM task: 64-byte POD, same bytes on host and device.
+ * Ranges are half-open and refer to the logical op(A) . op(B). */
+typedef struct {
+  uint32_t gemm_id;      /* caller's label for the GEMM this plan belongs to */
+  uint32_t tile_id;      /* index of the output tile, canonical order */
+  uint32_t m0, m_len;    /* rows of op(A) / of the output tile */
+  uint32_t n0, n_len;    /* columns of op(B) / of the output tile */
+  uint32_t k0, k_len;    /* chunk of the inner dimension */
+  uint32_t ksplit_idx;   /* s: which chunk */
+  uint32_t ksplit_cnt;   /* S: chunks of this tile */
+  uint64_t partial_off;  /* element offset of this task's m_len x n_len fp32 block */
+  uint32_t flags;        /* 0 */
+  uint32_t reserved[3];  /* 0 */
+} cleave_task;
+
+typedef struct cleave_plan cleave_plan; /* opaque, host-owned */
+
+/* ---- plan --------------------------------------------------------------
+ * Canonical task order: tile rows outermost, tile columns next, chunk index s
+ * innermost; tile_id is the running tile index; partial_off is the running
+ * sum of m_len*n_len, so a tile's S blocks are adjacent and each block is a
+ * contiguous row-major m_len x n_len array.
+ * Chunks: kc = ceil(K/S); chunk s = [s*kc, min((s+1)*kc, K)); a split with
+ * (S-1)*kc >= K (an empty chunk) is CLEAVE_EINVAL.
+ */
+
+/* Uniform tiling: ceil(M/tile_m) x ceil(N/tile_n) tiles, the last row and
+ * column of tiles clipped (never padded).  All arguments host values; *out is
+ * a new plan the caller destroys with cleave_plan_destroy.
+ * CLEAVE_EINVAL: a non-positive size, a dimension above 2^31-1, an empty
+ * chunk, out == NULL. */
+int cleave_plan_uniform(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
+                        int32_t ksplit, uint32_t gemm_id, cleave_plan** out);
+
+/* Explicit (heterogeneous) tiling: n_bands row bands of heights band_h[b]
+ * (sum M); band b is cut into n_cols[b] columns whose widths are listed
+ * consecutively in col_w (each band's widths sum to N); ksplit_per_tile has
+ * one S per tile in band-major order.  All arrays are host memory, read only
+ * during the call.  CLEAVE_EINVAL as above, or lists that do not sum to M / N,
+ * or an empty band / column. */
+int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_bands, const int64_t* band_h,
+                         const int32_t* n_cols, const int64_t* col_w,
+                         const int32_t* ksplit_per_tile, uint32_t gemm_id, cleave_plan** out);
+
+int64_t cleave_plan_num_tasks(const cleave_plan* plan);
+int64_t cleave_plan_num_tiles(const cleave_plan* plan);
+/* Host array of num_tasks records; borrowed, valid until cleave_plan_destroy. */
+const cleave_task* cleave_plan_tasks(const cleave_plan* plan);
+/* Number of fp32 elements the caller must provide as `partials`. */
+int64_t cleave_plan_partial_elems(const cleave_plan* plan);
+/* M, N, K of the plan into dims[0..2] (host). */
+int cleave_plan_dims(const cleave_plan* plan, int64_t* dims);
+/* Copies the plan's tables to the current device now (blocking). */
+int cleave_plan_upload(cleave_plan* plan);
+/* Frees host and device tables.  NULL is allowed.  Work already enqueued that
+ * uses the plan must have finished. */
+void cleave_plan_destroy(cleave_plan* plan);
+
+/* ---- execute -------------------------------------------------------------
+ * Runs the tasks task_ids[0..n_ids) (host array of indices into the plan's
+ * task list, any order, CLEAVE_EINVAL on an index out of range or a repeated
+ * index) or, with task_ids == NULL and n_ids == 0, all tasks.  Writes exactly
+ * the partial blocks of those tasks into `partials` (device, fp32,
+ * cleave_plan_partial_elems elements) and nothing else.
+ * A, B: device, dtype elements (4-byte aligned for F32, 2-byte for BF16; rows
+ * that start on 16-byte boundaries and inner chunks that are multiples of 16
+ * bytes take the fast path, anything else a slower guarded path).
+ * The bits of a task's block depend only on its record, the operands and
+ * dtype/layout -- not on which other tasks run in the same call. */
+int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                   const void* A, int64_t lda, int transA,
+                   const void* B, int64_t ldb, int transB,
+                   int dtype, float* partials, void* hip_stream);
+
+/* ---- reduce --------------------------------------------------------------
+ * C[m0+i, n0+j] = ((P_0[i,j] + P_1[i,j]) + ...) + P_{S-1}[i,j] for every tile.
+ * partials: device fp32, as written by cleave_execute.  C: device, M x N
+ * row-major with leading dimension ldc (>= N), out_dtype CLEAVE_F32 or
+ * CLEAVE_BF16 (round to nearest even of the fp32 sum).  With S = 1 the fp32
+ * output is a bitwise copy of the single partial. */
+int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
+                  int out_dtype, void* hip_stream);
+
+/* ---- misc ----------------------------------------------------------------*/
+const char* cleave_strerror(int status);
+/* hipError_t value of the most recent CLEAVE_EHIP on this thread (0 if none). */
+int cleave_last_hip_error(void);
+/* Library ABI version (major*100 + minor). */
+int cleave_version(void);
+/* Name of the kernel variant the last cleave_execute of this plan chose for
+ * its dominant launch (for profiling reports); static string, never NULL. */
+const char* cleave_plan_last_kernel(const cleave_plan* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLEAVE_H */

@@ -1,0 +1,217 @@
+"""ctypes binding of libcleave.so: argument marshalling only.
+
+Every step of the path (task generation, sub-GEMM execution, aggregation) runs
+inside the library; torch tensors are used here solely as owners of device
+memory and as the source of the current HIP stream.  There is no fallback: if
+the library has not been built, importing this module raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcleave.so")
+
+F32 = 0
+BF16 = 1
+
+OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
+
+# Byte layout of `cleave_task` (include/cleave.h).
+TASK_DTYPE = np.dtype([
+    ("gemm_id", "<u4"), ("tile_id", "<u4"),
+    ("m0", "<u4"), ("m_len", "<u4"), ("n0", "<u4"), ("n_len", "<u4"),
+    ("k0", "<u4"), ("k_len", "<u4"),
+    ("ksplit_idx", "<u4"), ("ksplit_cnt", "<u4"),
+    ("partial_off", "<u8"),
+    ("flags", "<u4"), ("reserved", "<u4", (3,)),
+])
+assert TASK_DTYPE.itemsize == 64
+
+EXPORTS = (
+    "cleave_plan_uniform", "cleave_plan_explicit", "cleave_plan_num_tasks",
+    "cleave_plan_num_tiles", "cleave_plan_tasks", "cleave_plan_partial_elems",
+    "cleave_plan_dims", "cleave_plan_upload", "cleave_plan_destroy", "cleave_execute",
+    "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
+    "cleave_plan_last_kernel",
+)
+
+
+class CleaveError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = _lib.cleave_strerror(status).decode()
+        if status == EHIP:
+            msg += " (hipError_t %d)" % _lib.cleave_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libcleave.so is not built: run `python -m paper_2512_22142_amd.build` "
+            "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, u32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p
+    lib.cleave_plan_uniform.argtypes = [i64, i64, i64, i64, i64, i32, u32, ctypes.POINTER(p)]
+    lib.cleave_plan_uniform.restype = ctypes.c_int
+    lib.cleave_plan_explicit.argtypes = [i64, i64, i64, i32, p, p, p, p, u32, ctypes.POINTER(p)]
+    lib.cleave_plan_explicit.restype = ctypes.c_int
+    for name in ("cleave_plan_num_tasks", "cleave_plan_num_tiles", "cleave_plan_partial_elems"):
+        getattr(lib, name).argtypes = [p]
+        getattr(lib, name).restype = i64
+    lib.cleave_plan_tasks.argtypes = [p]
+    lib.cleave_plan_tasks.restype = p
+    lib.cleave_plan_dims.argtypes = [p, p]
+    lib.cleave_plan_dims.restype = ctypes.c_int
+    lib.cleave_plan_upload.argtypes = [p]
+    lib.cleave_plan_upload.restype = ctypes.c_int
+    lib.cleave_plan_destroy.argtypes = [p]
+    lib.cleave_plan_destroy.restype = None
+    lib.cleave_execute.argtypes = [p, p, i64, p, i64, ctypes.c_int, p, i64, ctypes.c_int,
+                                   ctypes.c_int, p, p]
+    lib.cleave_execute.restype = ctypes.c_int
+    lib.cleave_reduce.argtypes = [p, p, p, i64, ctypes.c_int, p]
+    lib.cleave_reduce.restype = ctypes.c_int
+    lib.cleave_strerror.argtypes = [ctypes.c_int]
+    lib.cleave_strerror.restype = ctypes.c_char_p
+    lib.cleave_last_hip_error.argtypes = []
+    lib.cleave_last_hip_error.restype = ctypes.c_int
+    lib.cleave_version.argtypes = []
+    lib.cleave_version.restype = ctypes.c_int
+    lib.cleave_plan_last_kernel.argtypes = [p]
+    lib.cleave_plan_last_kernel.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status, where):
+    if status != OK:
+        raise CleaveError(status, where)
+
+
+class Plan:
+    """Owns a `cleave_plan*`."""
+
+    def __init__(self, handle):
+        self._h = ctypes.c_void_p(handle)
+        dims = (ctypes.c_int64 * 3)()
+        _check(_lib.cleave_plan_dims(self._h, dims), "cleave_plan_dims")
+        self.M, self.N, self.K = int(dims[0]), int(dims[1]), int(dims[2])
+        self.num_tasks = int(_lib.cleave_plan_num_tasks(self._h))
+        self.num_tiles = int(_lib.cleave_plan_num_tiles(self._h))
+        self.partial_elems = int(_lib.cleave_plan_partial_elems(self._h))
+
+    @property
+    def tasks(self):
+        """Copy of the task list as a structured numpy array."""
+        ptr = _lib.cleave_plan_tasks(self._h)
+        buf = (ctypes.c_char * (self.num_tasks * TASK_DTYPE.itemsize)).from_address(ptr)
+        return np.frombuffer(buf, dtype=TASK_DTYPE).copy()
+
+    def upload(self):
+        _check(_lib.cleave_plan_upload(self._h), "cleave_plan_upload")
+
+    @property
+    def last_kernel(self):
+        return _lib.cleave_plan_last_kernel(self._h).decode()
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            _lib.cleave_plan_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def plan_uniform(M, N, K, tile_m, tile_n, ksplit, gemm_id=0):
+    out = ctypes.c_void_p()
+    _check(_lib.cleave_plan_uniform(M, N, K, tile_m, tile_n, ksplit, gemm_id, ctypes.byref(out)),
+           "cleave_plan_uniform")
+    return Plan(out.value)
+
+
+def plan_explicit(M, N, K, band_h, col_w, ksplit_per_tile, gemm_id=0):
+    """band_h: band heights; col_w: one list of widths per band; ksplit_per_tile:
+    S per tile, band-major.  The lists are flattened into the C arrays."""
+    n_tiles = sum(len(w) for w in col_w)
+    if len(col_w) != len(band_h) or len(ksplit_per_tile) != n_tiles:
+        raise CleaveError(EINVAL, "plan_explicit (list lengths)")
+    bh = np.asarray(band_h, dtype=np.int64)
+    nc = np.asarray([len(w) for w in col_w], dtype=np.int32)
+    cw = np.asarray([x for w in col_w for x in w], dtype=np.int64)
+    ks = np.asarray(ksplit_per_tile, dtype=np.int32)
+    out = ctypes.c_void_p()
+    _check(_lib.cleave_plan_explicit(M, N, K, len(bh), bh.ctypes.data, nc.ctypes.data,
+                                     cw.ctypes.data, ks.ctypes.data, gemm_id, ctypes.byref(out)),
+           "cleave_plan_explicit")
+    return Plan(out.value)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _matrix(t, what):
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise ValueError("%s must be a 2-D device tensor with unit column stride" % what)
+    return ctypes.c_void_p(t.data_ptr()), int(t.stride(0))
+
+
+def execute(plan, A, B, partials, transA=0, transB=0, task_ids=None, stream=None):
+    """cleave_execute: A, B stored device matrices (torch), partials a flat fp32
+    device tensor of plan.partial_elems elements."""
+    import torch
+    a_ptr, lda = _matrix(A, "A")
+    b_ptr, ldb = _matrix(B, "B")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    if partials.dtype != torch.float32 or not partials.is_cuda or not partials.is_contiguous() \
+            or partials.numel() < plan.partial_elems:
+        raise ValueError("partials must be a contiguous fp32 device tensor of partial_elems elements")
+    # Stored shapes must hold the logical operands.
+    a_rows, a_cols = (plan.K, plan.M) if transA else (plan.M, plan.K)
+    b_rows, b_cols = (plan.N, plan.K) if transB else (plan.K, plan.N)
+    if tuple(A.shape) != (a_rows, a_cols) or tuple(B.shape) != (b_rows, b_cols):
+        raise ValueError("operand shapes %s, %s do not match the plan" % (tuple(A.shape), tuple(B.shape)))
+    ids_ptr, n_ids = None, 0
+    if task_ids is not None:
+        ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+        ids_ptr, n_ids = ctypes.c_void_p(ids.ctypes.data), len(ids)
+    _check(_lib.cleave_execute(plan._h, ids_ptr, n_ids, a_ptr, lda, int(transA), b_ptr, ldb,
+                               int(transB), _dtype_code(A), ctypes.c_void_p(partials.data_ptr()),
+                               _stream_ptr(stream)), "cleave_execute")
+
+
+def reduce(plan, partials, C, stream=None):
+    """cleave_reduce: C an M x N device matrix (fp32 or bf16)."""
+    c_ptr, ldc = _matrix(C, "C")
+    if tuple(C.shape) != (plan.M, plan.N):
+        raise ValueError("C must be M x N")
+    _check(_lib.cleave_reduce(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
+                              _dtype_code(C), _stream_ptr(stream)), "cleave_reduce")
+
+
+def version():
+    return int(_lib.cleave_version())

@@ -1,0 +1,41 @@
+// Launch interface between the C-ABI layer and the HIP kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "plan_internal.h"
+
+namespace cleave {
+
+struct ExecuteArgs {
+  const cleave_task* tasks;   // device task table
+  const WorkItem* items;      // device work items of one tile class
+  int64_t n_items;
+  const void* A;
+  const void* B;
+  int64_t lda, ldb;           // elements
+  int transA, transB;
+  float* partials;
+};
+
+// Enqueues the execute kernel for one tile class.  `vec` selects the 16-byte
+// load path (caller has checked alignment and divisibility).
+hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
+                          hipStream_t stream);
+
+struct ReduceArgs {
+  const cleave_task* tasks;
+  const ReduceItem* items;
+  int64_t n_items;
+  const float* partials;
+  void* C;
+  int64_t ldc;                // elements
+};
+
+// Enqueues the aggregation kernel.  `vec` selects the float4 path.
+hipError_t launch_reduce(const ReduceArgs& args, int out_dtype, bool vec, int grid,
+                         hipStream_t stream);
+
+}  // namespace cleave

@@ -1,0 +1,204 @@
+// Host-side task generation: row blocks of A x column blocks of B x chunks of
+// the inner dimension (paper Sec. 3.2 "Seamless training", Sec. 4.1 "Search
+// space of GEMM"; coverage and zero-task constraints of Sec. 4.1).
+#include <algorithm>
+#include <limits>
+#include <new>
+
+#include "plan_internal.h"
+
+namespace cleave {
+
+namespace {
+
+struct Tile {
+  int64_t m0, m_len, n0, n_len;
+  int32_t ksplit;
+};
+
+constexpr int64_t kMaxDim = std::numeric_limits<int32_t>::max();
+
+bool valid_split(int64_t K, int64_t S) {
+  if (S < 1 || S > K) return false;
+  const int64_t kc = (K + S - 1) / S;
+  return (S - 1) * kc < K;
+}
+
+// Emits the task records of `tiles` in canonical order and fills the derived
+// tables.  Returns a status code.
+int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles, uint32_t gemm_id,
+                cleave_plan** out) {
+  cleave_plan* p = new (std::nothrow) cleave_plan;
+  if (!p) return CLEAVE_ENOMEM;
+  try {
+    p->M = M;
+    p->N = N;
+    p->K = K;
+    p->num_tiles = static_cast<int64_t>(tiles.size());
+    uint64_t off = 0;
+    uint32_t tile_id = 0;
+    for (const Tile& tl : tiles) {
+      const int64_t S = tl.ksplit;
+      const int64_t kc = (K + S - 1) / S;
+      for (int64_t s = 0; s < S; ++s) {
+        cleave_task t{};
+        t.gemm_id = gemm_id;
+        t.tile_id = tile_id;
+        t.m0 = static_cast<uint32_t>(tl.m0);
+        t.m_len = static_cast<uint32_t>(tl.m_len);
+        t.n0 = static_cast<uint32_t>(tl.n0);
+        t.n_len = static_cast<uint32_t>(tl.n_len);
+        t.k0 = static_cast<uint32_t>(s * kc);
+        t.k_len = static_cast<uint32_t>(std::min(kc, K - s * kc));
+        t.ksplit_idx = static_cast<uint32_t>(s);
+        t.ksplit_cnt = static_cast<uint32_t>(S);
+        t.partial_off = off;
+        off += static_cast<uint64_t>(tl.m_len) * static_cast<uint64_t>(tl.n_len);
+        p->tasks.push_back(t);
+      }
+      ++tile_id;
+    }
+    p->partial_elems = static_cast<int64_t>(off);
+
+    for (const cleave_task& t : p->tasks) {
+      const uint32_t k_or = t.k0 | t.k_len;
+      const uint32_t mn_or = t.m0 | t.m_len | t.n0 | t.n_len;
+      p->all_k_mult8 &= (k_or % 8 == 0);
+      p->all_k_mult4 &= (k_or % 4 == 0);
+      p->all_mn_mult8 &= (mn_or % 8 == 0);
+      p->all_mn_mult4 &= (mn_or % 4 == 0);
+      p->all_n_mult4 &= ((t.n0 | t.n_len) % 4 == 0);
+    }
+
+    // Launch tables.  Execution order is free (only the task list's order is
+    // part of the interface): chunk index outermost, so that work items in
+    // flight at the same time read the same chunk of the inner dimension and
+    // share row panels of A / column panels of B in cache.
+    std::vector<uint32_t> order(p->tasks.size());
+    for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+      return p->tasks[a].ksplit_idx < p->tasks[b].ksplit_idx;
+    });
+    for (uint32_t idx : order) append_work_items(p->tasks[idx], idx, p->items);
+
+    constexpr uint32_t kReduceElemsPerItem = 16384;
+    for (uint32_t i = 0; i < p->tasks.size(); ++i) {
+      const cleave_task& t = p->tasks[i];
+      if (t.ksplit_idx != 0) continue;
+      const uint32_t rows_per = std::max<uint32_t>(1, kReduceElemsPerItem / t.n_len);
+      for (uint32_t r = 0; r < t.m_len; r += rows_per) {
+        p->reduce_items.push_back(ReduceItem{i, r, std::min(rows_per, t.m_len - r), 0});
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return CLEAVE_ENOMEM;
+  }
+  *out = p;
+  return CLEAVE_OK;
+}
+
+}  // namespace
+
+void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out) {
+  const int cls = tile_class_of(t);
+  const uint32_t edge = static_cast<uint32_t>(tile_edge(cls));
+  const uint64_t sm = (t.m_len + edge - 1) / edge;
+  const uint64_t sn = (t.n_len + edge - 1) / edge;
+  for (uint64_t s = 0; s < sm * sn; ++s)
+    out[cls].push_back(WorkItem{task_index, static_cast<uint32_t>(s)});
+}
+
+}  // namespace cleave
+
+using cleave::Tile;
+
+extern "C" int cleave_plan_uniform(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
+                                   int32_t ksplit, uint32_t gemm_id, cleave_plan** out) {
+  if (!out) return CLEAVE_EINVAL;
+  if (M < 1 || N < 1 || K < 1 || tile_m < 1 || tile_n < 1) return CLEAVE_EINVAL;
+  if (M > cleave::kMaxDim || N > cleave::kMaxDim || K > cleave::kMaxDim) return CLEAVE_EINVAL;
+  if (!cleave::valid_split(K, ksplit)) return CLEAVE_EINVAL;
+  std::vector<Tile> tiles;
+  try {
+    for (int64_t m0 = 0; m0 < M; m0 += tile_m)
+      for (int64_t n0 = 0; n0 < N; n0 += tile_n)
+        tiles.push_back(Tile{m0, std::min(tile_m, M - m0), n0, std::min(tile_n, N - n0), ksplit});
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  return cleave::finish_plan(M, N, K, tiles, gemm_id, out);
+}
+
+extern "C" int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_bands,
+                                    const int64_t* band_h, const int32_t* n_cols,
+                                    const int64_t* col_w, const int32_t* ksplit_per_tile,
+                                    uint32_t gemm_id, cleave_plan** out) {
+  if (!out || !band_h || !n_cols || !col_w || !ksplit_per_tile) return CLEAVE_EINVAL;
+  if (M < 1 || N < 1 || K < 1 || n_bands < 1) return CLEAVE_EINVAL;
+  if (M > cleave::kMaxDim || N > cleave::kMaxDim || K > cleave::kMaxDim) return CLEAVE_EINVAL;
+  std::vector<Tile> tiles;
+  try {
+    int64_t m0 = 0;
+    int64_t w_idx = 0;
+    for (int32_t b = 0; b < n_bands; ++b) {
+      const int64_t h = band_h[b];
+      if (h < 1 || h > M - m0 || n_cols[b] < 1) return CLEAVE_EINVAL;
+      int64_t n0 = 0;
+      for (int32_t c = 0; c < n_cols[b]; ++c, ++w_idx) {
+        const int64_t w = col_w[w_idx];
+        if (w < 1 || w > N - n0) return CLEAVE_EINVAL;
+        const int32_t S = ksplit_per_tile[tiles.size()];
+        if (!cleave::valid_split(K, S)) return CLEAVE_EINVAL;
+        tiles.push_back(Tile{m0, h, n0, w, S});
+        n0 += w;
+      }
+      if (n0 != N) return CLEAVE_EINVAL;
+      m0 += h;
+    }
+    if (m0 != M) return CLEAVE_EINVAL;
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  return cleave::finish_plan(M, N, K, tiles, gemm_id, out);
+}
+
+extern "C" int64_t cleave_plan_num_tasks(const cleave_plan* plan) {
+  return plan ? static_cast<int64_t>(plan->tasks.size()) : CLEAVE_EINVAL;
+}
+
+extern "C" int64_t cleave_plan_num_tiles(const cleave_plan* plan) {
+  return plan ? plan->num_tiles : CLEAVE_EINVAL;
+}
+
+extern "C" const cleave_task* cleave_plan_tasks(const cleave_plan* plan) {
+  return plan ? plan->tasks.data() : nullptr;
+}
+
+extern "C" int64_t cleave_plan_partial_elems(const cleave_plan* plan) {
+  return plan ? plan->partial_elems : CLEAVE_EINVAL;
+}
+
+extern "C" int cleave_plan_dims(const cleave_plan* plan, int64_t* dims) {
+  if (!plan || !dims) return CLEAVE_EINVAL;
+  dims[0] = plan->M;
+  dims[1] = plan->N;
+  dims[2] = plan->K;
+  return CLEAVE_OK;
+}
+
+extern "C" const char* cleave_plan_last_kernel(const cleave_plan* plan) {
+  return plan ? plan->last_kernel : "none";
+}
+
+extern "C" const char* cleave_strerror(int status) {
+  switch (status) {
+    case CLEAVE_OK: return "ok";
+    case CLEAVE_EINVAL: return "invalid argument";
+    case CLEAVE_ENOMEM: return "out of memory";
+    case CLEAVE_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int cleave_version(void) { return 100; }

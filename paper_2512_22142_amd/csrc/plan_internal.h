@@ -1,0 +1,69 @@
+// Internal layout of a plan: host task list plus the launch tables derived
+// from it, and their lazily created device copies.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "cleave.h"
+
+namespace cleave {
+
+// Workgroup tile classes of the execute kernel.  Which class a task uses is a
+// pure function of its record (see tile_class_of), so a re-issued task is cut
+// into the same sub-tiles no matter which other tasks share the launch.
+enum TileClass : int { kTileLarge = 0 /* 256 x 256 */, kTileSmall = 1 /* 128 x 128 */, kNumTileClasses = 2 };
+
+inline int tile_edge(int cls) { return cls == kTileLarge ? 256 : 128; }
+
+inline int tile_class_of(const cleave_task& t) {
+  return (t.m_len > 128 && t.n_len > 128) ? kTileLarge : kTileSmall;
+}
+
+// One unit of work of the execute kernel: a sub-tile of one task's output
+// block, computed over the task's whole chunk of the inner dimension.
+struct WorkItem {
+  uint32_t task;    // index into the task table
+  uint32_t sub;     // sub-tile index within the task's block, row-major over
+                    // ceil(m_len/edge) x ceil(n_len/edge) sub-tiles
+};
+static_assert(sizeof(WorkItem) == 8, "WorkItem is 8 bytes");
+
+// One unit of work of the reduce kernel: a run of rows of one output tile.
+struct ReduceItem {
+  uint32_t task;    // index of the tile's chunk-0 task
+  uint32_t row0;    // first row within the tile
+  uint32_t rows;    // number of rows
+  uint32_t pad;
+};
+static_assert(sizeof(ReduceItem) == 16, "ReduceItem is 16 bytes");
+
+// Appends the work items of `task_index` (record t) to out[class].
+void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out);
+
+}  // namespace cleave
+
+struct cleave_plan {
+  int64_t M = 0, N = 0, K = 0;
+  int64_t partial_elems = 0;
+  int64_t num_tiles = 0;
+  bool all_k_mult8 = true;   // every k0 and k_len is a multiple of 8
+  bool all_k_mult4 = true;
+  bool all_mn_mult8 = true;  // every m0, m_len, n0, n_len is a multiple of 8
+  bool all_mn_mult4 = true;
+  bool all_n_mult4 = true;   // every n0, n_len multiple of 4 (vector path of reduce)
+  std::vector<cleave_task> tasks;
+  std::vector<cleave::WorkItem> items[cleave::kNumTileClasses];  // all tasks, launch order
+  std::vector<cleave::ReduceItem> reduce_items;
+
+  // Device copies (current device at first use).
+  int device = -1;
+  cleave_task* d_tasks = nullptr;
+  cleave::WorkItem* d_items[cleave::kNumTileClasses] = {nullptr, nullptr};
+  cleave::ReduceItem* d_reduce_items = nullptr;
+  // Scratch for subset launches; grown on demand, reused by later calls.
+  cleave::WorkItem* d_subset_items = nullptr;
+  int64_t d_subset_capacity = 0;
+
+  const char* last_kernel = "none";
+};
