@@ -82,16 +82,22 @@ int compute_units(int* out) {
 
 const char* kernel_name(int dtype, int cls, bool vec, int transA, int transB) {
   static const char* names[2][2][5] = {
-      {{"execute_f32_256_nn", "execute_f32_256_nt", "execute_f32_256_tn", "execute_f32_256_tt",
-        "execute_f32_256_scalar"},
-       {"execute_f32_128_nn", "execute_f32_128_nt", "execute_f32_128_tn", "execute_f32_128_tt",
-        "execute_f32_128_scalar"}},
-      {{"execute_bf16_256_nn", "execute_bf16_256_nt", "execute_bf16_256_tn", "execute_bf16_256_tt",
-        "execute_bf16_256_scalar"},
-       {"execute_bf16_128_nn", "execute_bf16_128_nt", "execute_bf16_128_tn", "execute_bf16_128_tt",
-        "execute_bf16_128_scalar"}}};
+      {{"execute_f32_256x128_nn", "execute_f32_256x128_nt", "execute_f32_256x128_tn", "execute_f32_256x128_tt",
+        "execute_f32_256x128_scalar"},
+       {"execute_f32_128x128_nn", "execute_f32_128x128_nt", "execute_f32_128x128_tn", "execute_f32_128x128_tt",
+        "execute_f32_128x128_scalar"}},
+      {{"execute_bf16_256x128_nn", "execute_bf16_256x128_nt", "execute_bf16_256x128_tn", "execute_bf16_256x128_tt",
+        "execute_bf16_256x128_scalar"},
+       {"execute_bf16_128x128_nn", "execute_bf16_128x128_nt", "execute_bf16_128x128_tn", "execute_bf16_128x128_tt",
+        "execute_bf16_128x128_scalar"}}};
   const int mode = vec ? (transA ? 2 : 0) + (transB ? 1 : 0) : 4;
   return names[dtype == CLEAVE_BF16 ? 1 : 0][cls][mode];
+}
+
+const char* direct_kernel_name(int transA, int transB) {
+  static const char* names[4] = {"execute_direct_bf16_256x128_nn", "execute_direct_bf16_256x128_nt",
+                                 "execute_direct_bf16_256x128_tn", "execute_direct_bf16_256x128_tt"};
+  return names[(transA ? 2 : 0) + (transB ? 1 : 0)];
 }
 
 }  // namespace
@@ -148,7 +154,9 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
   const int e = 16 / eb;
   const bool vec = (e == 8 ? (plan->all_k_mult8 && plan->all_mn_mult8)
                            : (plan->all_k_mult4 && plan->all_mn_mult4)) &&
-                   lda % e == 0 && ldb % e == 0 && aligned(A, 16) && aligned(B, 16);
+                   lda % e == 0 && ldb % e == 0 && aligned(A, 16) && aligned(B, 16) &&
+                   // in-tile byte offsets are kept in 32 bits
+                   lda * eb < (int64_t{1} << 22) && ldb * eb < (int64_t{1} << 22);
 
   const cleave::WorkItem* d_lists[cleave::kNumTileClasses] = {plan->d_items[0], plan->d_items[1]};
   int64_t counts[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items[0].size()),
@@ -196,14 +204,20 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
     args.transA = transA;
     args.transB = transB;
     args.partials = partials;
-    // One resident workgroup per CU for the 256-edge tile (its LDS stages fill
-    // the CU), two for the 128-edge tile.
-    const int64_t resident = static_cast<int64_t>(cus) * (c == cleave::kTileLarge ? 1 : 2);
+    // Two resident workgroups per CU for the 256 x 128 tile (128 accumulator
+    // registers per lane, 54 KB of LDS each), four for the 128 x 128 tile.
+    const int64_t resident = static_cast<int64_t>(cus) * (c == cleave::kTileLarge ? 2 : 4);
     const int grid = static_cast<int>(std::min<int64_t>(counts[c], resident));
-    CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
+    const bool direct = vec && dtype == CLEAVE_BF16 && c == cleave::kTileLarge && plan->all_klen_mult32;
+    if (direct) {
+      CLEAVE_HIP(cleave::launch_execute_direct(args, grid, stream));
+    } else {
+      CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
+    }
     if (counts[c] > most) {
       most = counts[c];
-      plan->last_kernel = kernel_name(dtype, c, vec, transA, transB);
+      plan->last_kernel = direct ? direct_kernel_name(transA, transB)
+                                 : kernel_name(dtype, c, vec, transA, transB);
     }
   }
   return CLEAVE_OK;

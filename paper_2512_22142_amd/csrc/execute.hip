@@ -2,19 +2,22 @@
 // rows of A with its columns of B; here restricted to its chunk of the inner
 // dimension, and the fp32 partial block goes to the task's slot in HBM).
 //
-// One workgroup (256 threads = 4 wave64, arranged 2 x 2) computes one work
-// item: an EDGE x EDGE sub-tile of a task's output block over the task's whole
-// chunk [k0, k0 + k_len).  The inner loop walks the chunk in ascending steps
-// of 128 bytes of K per row (64 bf16 / 32 fp32 elements); the order of the
-// MFMA accumulation for an output element therefore depends only on the task
-// record, which is what makes a re-issued task bitwise reproducible.
+// One workgroup (4 wave64, 2 x 2) computes one work item: a 256 x 128 (or
+// 128 x 128) sub-tile of a task's output block over the task's whole chunk
+// [k0, k0 + k_len).  A wave owns a 128 x 64 (64 x 64) patch.  The inner loop
+// walks the chunk in ascending steps of 128 bytes of K per row (64 bf16 / 32
+// fp32 elements) and, inside a step, in ascending 32-byte sub-steps; the order
+// of the MFMA accumulation for an output element therefore depends only on
+// the task record, which is what makes a re-issued task bitwise reproducible.
 //
-// Data path per K step: global -> VGPR (16-byte chunks, next step prefetched
-// while the current one is multiplied) -> LDS (K-contiguous rows, 16 bytes of
-// padding per row so that fragment reads are bank-conflict free; operands
-// whose storage is not K-contiguous are transposed in registers on the way)
-// -> 16-byte fragment reads -> MFMA 32x32x16 bf16 (or 32x32x2 fp32) into fp32
-// accumulators -> guarded stores of the partial block.
+// Data path per K step: global -> VGPR (16-byte chunks, issued one step
+// ahead) -> LDS (K-contiguous rows, 16 bytes of padding per row so that
+// fragment reads are bank-conflict free; operands whose storage is not
+// K-contiguous are transposed in registers on the way) -> 16-byte fragment
+// reads -> MFMA 32x32x16 bf16 (or 32x32x2 fp32) into fp32 accumulators ->
+// stores of the partial block.  Registers and LDS are sized so that two
+// workgroups share a CU: while one waits at a barrier, refills LDS or drains
+// its partial-block stores, the other keeps the matrix cores busy.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -29,63 +32,87 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
 constexpr int kChunksPerRow = 8;                    // 128 bytes of K per tile row and step
 constexpr int kRowStride = 16 * kChunksPerRow + 16; // LDS bytes per tile row (padded)
 
 // ---------------------------------------------------------------------------
 // Operand tile: R rows (an m or n index) x 128 bytes of K, moved global ->
-// registers -> LDS.  `row_stride` / `k_stride` are element strides of the
-// stored matrix along the tile's row index and along K.
+// registers -> LDS by NT threads.  `row_stride` / `k_stride` are element
+// strides of the stored matrix along the tile's row index and along K.
 // ---------------------------------------------------------------------------
 enum LoadMode : int { kVecKContig = 0, kVecTransposed = 1, kScalar = 2 };
 
-template <int EB, int R, int MODE>
+template <int EB, int R, int NT, int MODE>
 struct OperandTile {
   static constexpr int E = 16 / EB;                 // elements per 16-byte chunk
-  static constexpr int kStepElems = kChunksPerRow * E;
-  static constexpr int NV = R / 32;                 // chunks held per thread
-  static constexpr int kBlocks = kChunksPerRow * (R / E);   // E x E blocks (transposed mode)
-  static constexpr int kBlocksPerThread = (kBlocks + kThreads - 1) / kThreads;
-  static constexpr int NREG = MODE == kVecTransposed ? kBlocksPerThread * E : NV;
+  static constexpr int NV = R * kChunksPerRow / NT; // 16-byte chunks held per thread
+  // Transposed mode: a thread owns KB consecutive k rows x E consecutive tile
+  // rows (one 16-byte load per k row) and writes E runs of KB elements.
+  static constexpr int KB = (EB == 2) ? (NV < 8 ? NV : 8) : 4;
+  static constexpr int kBlocksPerThread = NV / KB;
+  static constexpr int KG = kChunksPerRow * E / KB; // k groups per step
+  static_assert(NV >= 2 && NV % KB == 0, "unsupported tile / thread count");
 
-  u32x4 v[NREG];
+  u32x4 v[NV];
+  uint32_t off[NV];   // vector modes: byte offset of each 16-byte load from the step base
 
-  // base: first element of the tile's row 0 at the chunk start k0 (bytes).
-  // r_valid: rows of the tile that exist; k_left: elements of K that remain
-  // from this step's start (>= 1).
-  __device__ __forceinline__ void load(const unsigned char* base, int64_t row_stride,
-                                       int64_t k_stride, int r_valid, int k_left, int t) {
+  // Vector modes: fixes this thread's load offsets for one work item.  Rows
+  // beyond r_valid are clamped to the last valid 16-byte run: they only feed
+  // output elements that are never stored.
+  __device__ __forceinline__ void init(int64_t row_stride, int64_t k_stride, int r_valid, int t) {
     if constexpr (MODE == kVecKContig) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int c = t + kThreads * i;
+        const int c = t + NT * i;
         const int row = min(c >> 3, r_valid - 1);
-        const int k = (c & 7) * E;
-        const unsigned char* p = base + (static_cast<int64_t>(row) * row_stride + k) * EB;
-        v[i] = (k < k_left) ? *reinterpret_cast<const u32x4*>(p) : u32x4{0, 0, 0, 0};
+        off[i] = static_cast<uint32_t>((row * row_stride + (c & 7) * E) * EB);
       }
     } else if constexpr (MODE == kVecTransposed) {
 #pragma unroll
       for (int b = 0; b < kBlocksPerThread; ++b) {
-        const int blk = t + kThreads * b;
-        const int kg = blk & 7;
-        const int rg = blk >> 3;
+        const int blk = t + NT * b;
+        const int kg = (blk >> 3) % KG;
+        const int rg = (blk / (8 * KG)) * 8 + (blk & 7);
         const int r = min(rg * E, r_valid - E);
 #pragma unroll
-        for (int kk = 0; kk < E; ++kk) {
-          const int k = kg * E + kk;
-          const unsigned char* p = base + (static_cast<int64_t>(k) * k_stride + r) * EB;
-          const bool ok = (kBlocks >= kThreads || blk < kBlocks) && k < k_left;
-          v[b * E + kk] = ok ? *reinterpret_cast<const u32x4*>(p) : u32x4{0, 0, 0, 0};
+        for (int kk = 0; kk < KB; ++kk)
+          off[b * KB + kk] = static_cast<uint32_t>(((kg * KB + kk) * k_stride + r) * EB);
+      }
+    }
+  }
+
+  // k index (within the step) of load i, for the tail predicate.
+  static __device__ __forceinline__ int k_of(int i, int t) {
+    if constexpr (MODE == kVecKContig) {
+      return ((t + NT * i) & 7) * E;
+    } else {
+      const int blk = t + NT * (i / KB);
+      return ((blk >> 3) % KG) * KB + (i % KB);
+    }
+  }
+
+  // base: first element of the tile's row 0 at this step's first k (bytes,
+  // wave-uniform).  FULL: the whole step lies inside the chunk; otherwise
+  // k_left (>= 1) elements remain and loads beyond them yield zeros.
+  template <bool FULL>
+  __device__ __forceinline__ void load(const unsigned char* base, int64_t row_stride,
+                                       int64_t k_stride, int r_valid, int k_left, int t) {
+    if constexpr (MODE != kScalar) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        if (FULL || k_of(i, t) < k_left) {
+          v[i] = *reinterpret_cast<const u32x4*>(base + off[i]);
+        } else {
+          v[i] = u32x4{0, 0, 0, 0};
         }
       }
     } else {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int c = t + kThreads * i;
+        const int c = t + NT * i;
         const int row = c >> 3;
         const int k = (c & 7) * E;
         u32x4 w = {0, 0, 0, 0};
@@ -115,17 +142,16 @@ struct OperandTile {
     if constexpr (MODE != kVecTransposed) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int c = t + kThreads * i;
+        const int c = t + NT * i;
         *reinterpret_cast<u32x4*>(lds + (c >> 3) * kRowStride + (c & 7) * 16) = v[i];
       }
     } else {
 #pragma unroll
       for (int b = 0; b < kBlocksPerThread; ++b) {
-        const int blk = t + kThreads * b;
-        if (kBlocks < kThreads && blk >= kBlocks) continue;
-        const int kg = blk & 7;
-        const int rg = blk >> 3;
-        unsigned char* dst = lds + (rg * E) * kRowStride + kg * 16;
+        const int blk = t + NT * b;
+        const int kg = (blk >> 3) % KG;
+        const int rg = (blk / (8 * KG)) * 8 + (blk & 7);
+        unsigned char* dst = lds + (rg * E) * kRowStride + kg * KB * EB;
         if constexpr (EB == 4) {
           // 4 x 4 transpose of dwords: pure renaming.
 #pragma unroll
@@ -134,18 +160,24 @@ struct OperandTile {
             *reinterpret_cast<u32x4*>(dst + j * kRowStride) = w;
           }
         } else {
-          // 8 x 8 transpose of 16-bit values: row j of the result collects
-          // halfword j of the eight loaded k rows.
+          // KB x 8 transpose of 16-bit values: row j of the result collects
+          // halfword j of the KB loaded k rows.
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            u32x4 w;
+            uint32_t w[KB / 2];
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              const uint32_t lo = v[b * 8 + 2 * p][j >> 1];
-              const uint32_t hi = v[b * 8 + 2 * p + 1][j >> 1];
+            for (int p = 0; p < KB / 2; ++p) {
+              const uint32_t lo = v[b * KB + 2 * p][j >> 1];
+              const uint32_t hi = v[b * KB + 2 * p + 1][j >> 1];
               w[p] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
             }
-            *reinterpret_cast<u32x4*>(dst + j * kRowStride) = w;
+            if constexpr (KB == 8) {
+              *reinterpret_cast<u32x4*>(dst + j * kRowStride) = u32x4{w[0], w[1], w[2], w[3]};
+            } else if constexpr (KB == 4) {
+              *reinterpret_cast<u32x2*>(dst + j * kRowStride) = u32x2{w[0], w[1]};
+            } else {
+              *reinterpret_cast<uint32_t*>(dst + j * kRowStride) = w[0];
+            }
           }
         }
       }
@@ -154,24 +186,30 @@ struct OperandTile {
 };
 
 // ---------------------------------------------------------------------------
-// The kernel.
+// The kernel.  A TM x TN workgroup tile computed by WM x WN waves; one LDS
+// stage (A tile then B tile), refilled from registers between two barriers.
+// Two (or more) workgroups are resident per CU, so one workgroup's barriers,
+// LDS refills and partial-block stores overlap with the other's MFMAs.
 // ---------------------------------------------------------------------------
-template <int EB, int EDGE, int MODE_A, int MODE_B>
-__global__ __launch_bounds__(kThreads) void execute_kernel(ExecuteArgs args) {
+template <int EB, int TM, int TN, int WM, int WN, int MODE_A, int MODE_B>
+__global__ __launch_bounds__(WM* WN * 64, 2) void execute_kernel(ExecuteArgs args) {
+  constexpr int NT = WM * WN * 64;
   constexpr int E = 16 / EB;
   constexpr int kStepElems = kChunksPerRow * E;
-  constexpr int WT = EDGE / 2;          // wave tile edge
-  constexpr int NBLK = WT / 32;         // 32 x 32 MFMA blocks per wave tile edge
-  constexpr int kTileBytes = EDGE * kRowStride;
-  constexpr int kStageBytes = 2 * kTileBytes;
+  constexpr int WTM = TM / WM;          // wave tile
+  constexpr int WTN = TN / WN;
+  constexpr int MB = WTM / 32;          // 32 x 32 MFMA blocks per wave tile
+  constexpr int NB = WTN / 32;
+  constexpr int kATileBytes = TM * kRowStride;
+  constexpr int kSub = kChunksPerRow / 2;   // 32-byte sub-steps per K step
 
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = t >> 6;
-  const int wm = wave >> 1;
-  const int wn = wave & 1;
+  const int wm = wave / WN;
+  const int wn = wave % WN;
   const int l32 = lane & 31;
   const int lh = lane >> 5;
 
@@ -181,16 +219,19 @@ __global__ __launch_bounds__(kThreads) void execute_kernel(ExecuteArgs args) {
   const int64_t b_rs = args.transB ? args.ldb : 1;
   const int64_t b_ks = args.transB ? 1 : args.ldb;
 
+  const unsigned char* a_frag = smem + (wm * WTM + l32) * kRowStride + lh * 16;
+  const unsigned char* b_frag = smem + kATileBytes + (wn * WTN + l32) * kRowStride + lh * 16;
+
   for (int64_t it = blockIdx.x; it < args.n_items; it += gridDim.x) {
     const WorkItem item = args.items[it];
     const cleave_task task = args.tasks[item.task];
-    const uint32_t sub_cols = (task.n_len + EDGE - 1) / EDGE;
+    const uint32_t sub_cols = (task.n_len + TN - 1) / TN;
     const uint32_t sub_m = item.sub / sub_cols;
     const uint32_t sub_n = item.sub - sub_m * sub_cols;
-    const int m_valid = min(static_cast<int>(task.m_len - sub_m * EDGE), EDGE);
-    const int n_valid = min(static_cast<int>(task.n_len - sub_n * EDGE), EDGE);
-    const int64_t m_base = static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * EDGE;
-    const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * EDGE;
+    const int m_valid = min(static_cast<int>(task.m_len - sub_m * TM), TM);
+    const int n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
+    const int64_t m_base = static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * TM;
+    const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * TN;
     const int k_len = static_cast<int>(task.k_len);
 
     const unsigned char* a_ptr = static_cast<const unsigned char*>(args.A) +
@@ -198,103 +239,145 @@ __global__ __launch_bounds__(kThreads) void execute_kernel(ExecuteArgs args) {
     const unsigned char* b_ptr = static_cast<const unsigned char*>(args.B) +
                                  (n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * EB;
 
-    f32x16 acc[NBLK][NBLK];
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < NBLK; ++j)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    OperandTile<EB, EDGE, MODE_A> ta;
-    OperandTile<EB, EDGE, MODE_B> tb;
+    OperandTile<EB, TM, NT, MODE_A> ta;
+    OperandTile<EB, TN, NT, MODE_B> tb;
+    ta.init(a_rs, a_ks, m_valid, t);
+    tb.init(b_rs, b_ks, n_valid, t);
+
+    // Global -> registers for step s; full steps take the unpredicated path.
+    auto load_step = [&](int s) {
+      const int64_t koff = static_cast<int64_t>(s) * kStepElems;
+      const int k_left = k_len - static_cast<int>(koff);
+      const unsigned char* pa = a_ptr + koff * a_ks * EB;
+      const unsigned char* pb = b_ptr + koff * b_ks * EB;
+      if (k_left >= kStepElems) {
+        ta.template load<true>(pa, a_rs, a_ks, m_valid, k_left, t);
+        tb.template load<true>(pb, b_rs, b_ks, n_valid, k_left, t);
+      } else {
+        ta.template load<false>(pa, a_rs, a_ks, m_valid, k_left, t);
+        tb.template load<false>(pb, b_rs, b_ks, n_valid, k_left, t);
+      }
+    };
+    auto store_step = [&]() {
+      ta.store(smem, t);
+      tb.store(smem + kATileBytes, t);
+    };
+    u32x4 fa[2][MB], fb[2][NB];
+    auto read_frags = [&](int ks, int buf) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+        fa[buf][i] = *reinterpret_cast<const u32x4*>(a_frag + i * 32 * kRowStride + ks * 32);
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        fb[buf][j] = *reinterpret_cast<const u32x4*>(b_frag + j * 32 * kRowStride + ks * 32);
+    };
+    auto mma = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          if constexpr (EB == 2) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]),
+                acc[i][j], 0, 0, 0);
+          } else {
+            // (bit-cast the whole chunk first: a bit_cast of a single vector
+            // element lvalue is miscompiled into a read of element 0)
+            const f32x4 a4 = __builtin_bit_cast(f32x4, fa[buf][i]);
+            const f32x4 b4 = __builtin_bit_cast(f32x4, fb[buf][j]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], b4[e], acc[i][j], 0, 0, 0);
+          }
+        }
+      }
+    };
 
     const int steps = (k_len + kStepElems - 1) / kStepElems;
-    ta.load(a_ptr, a_rs, a_ks, m_valid, k_len, t);
-    tb.load(b_ptr, b_rs, b_ks, n_valid, k_len, t);
-    ta.store(smem, t);
-    tb.store(smem + kTileBytes, t);
+    load_step(0);
+    // Every wave has finished reading the previous work item's last tile.
+    __syncthreads();
+    store_step();
     __syncthreads();
 
     for (int s = 0; s < steps; ++s) {
-      unsigned char* cur = smem + (s & 1) * kStageBytes;
-      unsigned char* nxt = smem + ((s + 1) & 1) * kStageBytes;
       const bool more = s + 1 < steps;
-      if (more) {
-        const int64_t koff = static_cast<int64_t>(s + 1) * kStepElems;
-        const int k_left = k_len - static_cast<int>(koff);
-        ta.load(a_ptr + koff * a_ks * EB, a_rs, a_ks, m_valid, k_left, t);
-        tb.load(b_ptr + koff * b_ks * EB, b_rs, b_ks, n_valid, k_left, t);
-      }
-
-      const unsigned char* a_frag = cur + (wm * WT + l32) * kRowStride + lh * 16;
-      const unsigned char* b_frag = cur + kTileBytes + (wn * WT + l32) * kRowStride + lh * 16;
+      read_frags(0, 0);
+      if (more) load_step(s + 1);
 #pragma unroll
-      for (int ks = 0; ks < kChunksPerRow / 2; ++ks) {
-        u32x4 af[NBLK], bf[NBLK];
+      for (int ks = 0; ks < kSub; ++ks) {
+        if (ks + 1 < kSub) read_frags(ks + 1, (ks + 1) & 1);
+        mma(ks & 1);
+        if constexpr (EB == 2) {
+          // Issue order inside a sub-step: one fragment read of the next
+          // sub-step between consecutive MFMAs of this one.
+          if (ks + 1 < kSub) {
 #pragma unroll
-        for (int i = 0; i < NBLK; ++i)
-          af[i] = *reinterpret_cast<const u32x4*>(a_frag + i * 32 * kRowStride + ks * 32);
-#pragma unroll
-        for (int j = 0; j < NBLK; ++j)
-          bf[j] = *reinterpret_cast<const u32x4*>(b_frag + j * 32 * kRowStride + ks * 32);
-#pragma unroll
-        for (int i = 0; i < NBLK; ++i) {
-#pragma unroll
-          for (int j = 0; j < NBLK; ++j) {
-            if constexpr (EB == 2) {
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j],
-                  0, 0, 0);
-            } else {
-              // (bit-cast the whole chunk first: a bit_cast of a single vector
-              // element lvalue is miscompiled into a read of element 0)
-              const f32x4 a4 = __builtin_bit_cast(f32x4, af[i]);
-              const f32x4 b4 = __builtin_bit_cast(f32x4, bf[j]);
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], b4[e], acc[i][j], 0, 0, 0);
+            for (int x = 0; x < MB + NB; ++x) {
+              __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
           }
         }
       }
-
       if (more) {
-        ta.store(nxt, t);
-        tb.store(nxt + kTileBytes, t);
+        __syncthreads();     // all fragment reads of this step are done
+        store_step();
+        __syncthreads();     // the next step's tile is visible
       }
-      __syncthreads();
     }
 
     // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
-    // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r.
-    float* out = args.partials + task.partial_off;
+    // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
+    // half a wave writes one aligned 128-byte run per store.  One per-thread
+    // base pointer plus wave-uniform row offsets keeps the epilogue free of
+    // per-store address arithmetic.
     const int64_t ldp = task.n_len;
+    const int row0 = wm * WTM + lh * 4;
+    const int col0 = wn * WTN + l32;
+    float* tp = args.partials + task.partial_off +
+                (static_cast<int64_t>(sub_m) * TM + row0) * ldp + sub_n * TN + col0;
+    if (m_valid == TM && n_valid == TN) {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < NBLK; ++j) {
-        const int col = wn * WT + j * 32 + l32;
-        if (col >= n_valid) continue;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const int row = wm * WT + i * 32 + q * 8 + lh * 4 + r;
-            if (row < m_valid)
-              out[(static_cast<int64_t>(sub_m) * EDGE + row) * ldp + sub_n * EDGE + col] =
-                  acc[i][j][q * 4 + r];
+            float* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ldp;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) p[j * 32] = acc[i][j][q * 4 + r];
           }
-        }
-      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int rr = i * 32 + q * 8 + r;
+            float* p = tp + static_cast<int64_t>(rr) * ldp;
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              if (row0 + rr < m_valid && col0 + j * 32 < n_valid) p[j * 32] = acc[i][j][q * 4 + r];
+          }
     }
   }
 }
 
-template <int EB, int EDGE, int MODE_A, int MODE_B>
+template <int EB, int TM, int TN, int WM, int WN, int MODE_A, int MODE_B>
 hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
-  constexpr size_t lds = 2 * 2 * EDGE * kRowStride;
-  auto kern = execute_kernel<EB, EDGE, MODE_A, MODE_B>;
+  constexpr size_t lds = (TM + TN) * kRowStride;
+  auto kern = execute_kernel<EB, TM, TN, WM, WN, MODE_A, MODE_B>;
   static thread_local int configured_device = -1;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -305,19 +388,19 @@ hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
     if (e != hipSuccess) return e;
     configured_device = dev;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, args);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, stream, args);
   return hipGetLastError();
 }
 
-template <int EB, int EDGE>
+template <int EB, int TM, int TN, int WM, int WN>
 hipError_t launch_modes(const ExecuteArgs& args, bool vec, int grid, hipStream_t stream) {
-  if (!vec) return launch_one<EB, EDGE, kScalar, kScalar>(args, grid, stream);
+  if (!vec) return launch_one<EB, TM, TN, WM, WN, kScalar, kScalar>(args, grid, stream);
   const bool a_k = !args.transA;   // A stored M x K: K-contiguous
   const bool b_k = args.transB;    // B stored N x K: K-contiguous
-  if (a_k && b_k) return launch_one<EB, EDGE, kVecKContig, kVecKContig>(args, grid, stream);
-  if (a_k && !b_k) return launch_one<EB, EDGE, kVecKContig, kVecTransposed>(args, grid, stream);
-  if (!a_k && b_k) return launch_one<EB, EDGE, kVecTransposed, kVecKContig>(args, grid, stream);
-  return launch_one<EB, EDGE, kVecTransposed, kVecTransposed>(args, grid, stream);
+  if (a_k && b_k) return launch_one<EB, TM, TN, WM, WN, kVecKContig, kVecKContig>(args, grid, stream);
+  if (a_k && !b_k) return launch_one<EB, TM, TN, WM, WN, kVecKContig, kVecTransposed>(args, grid, stream);
+  if (!a_k && b_k) return launch_one<EB, TM, TN, WM, WN, kVecTransposed, kVecKContig>(args, grid, stream);
+  return launch_one<EB, TM, TN, WM, WN, kVecTransposed, kVecTransposed>(args, grid, stream);
 }
 
 }  // namespace
@@ -325,11 +408,11 @@ hipError_t launch_modes(const ExecuteArgs& args, bool vec, int grid, hipStream_t
 hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
                           hipStream_t stream) {
   if (dtype == CLEAVE_BF16) {
-    return tile_class == kTileLarge ? launch_modes<2, 256>(args, vec, grid, stream)
-                                    : launch_modes<2, 128>(args, vec, grid, stream);
+    return tile_class == kTileLarge ? launch_modes<2, 256, 128, 2, 2>(args, vec, grid, stream)
+                                    : launch_modes<2, 128, 128, 2, 2>(args, vec, grid, stream);
   }
-  return tile_class == kTileLarge ? launch_modes<4, 256>(args, vec, grid, stream)
-                                  : launch_modes<4, 128>(args, vec, grid, stream);
+  return tile_class == kTileLarge ? launch_modes<4, 256, 128, 2, 2>(args, vec, grid, stream)
+                                  : launch_modes<4, 128, 128, 2, 2>(args, vec, grid, stream);
 }
 
 }  // namespace cleave

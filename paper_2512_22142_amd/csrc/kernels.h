@@ -25,6 +25,11 @@ struct ExecuteArgs {
 hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
                           hipStream_t stream);
 
+// Enqueues the bf16 direct-to-LDS execute kernel (256 x 128 tiles).  The
+// caller has checked the 16-byte load conditions and that every chunk length
+// is a multiple of 32 elements.
+hipError_t launch_execute_direct(const ExecuteArgs& args, int grid, hipStream_t stream);
+
 struct ReduceArgs {
   const cleave_task* tasks;
   const ReduceItem* items;

@@ -65,6 +65,7 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
       const uint32_t mn_or = t.m0 | t.m_len | t.n0 | t.n_len;
       p->all_k_mult8 &= (k_or % 8 == 0);
       p->all_k_mult4 &= (k_or % 4 == 0);
+      p->all_klen_mult32 &= (t.k_len % 32 == 0);
       p->all_mn_mult8 &= (mn_or % 8 == 0);
       p->all_mn_mult4 &= (mn_or % 4 == 0);
       p->all_n_mult4 &= ((t.n0 | t.n_len) % 4 == 0);
@@ -102,9 +103,10 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
 
 void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out) {
   const int cls = tile_class_of(t);
-  const uint32_t edge = static_cast<uint32_t>(tile_edge(cls));
-  const uint64_t sm = (t.m_len + edge - 1) / edge;
-  const uint64_t sn = (t.n_len + edge - 1) / edge;
+  const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
+  const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
+  const uint64_t sm = (t.m_len + tr - 1) / tr;
+  const uint64_t sn = (t.n_len + tc - 1) / tc;
   for (uint64_t s = 0; s < sm * sn; ++s)
     out[cls].push_back(WorkItem{task_index, static_cast<uint32_t>(s)});
 }

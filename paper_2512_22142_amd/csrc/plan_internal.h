@@ -12,20 +12,19 @@ namespace cleave {
 // Workgroup tile classes of the execute kernel.  Which class a task uses is a
 // pure function of its record (see tile_class_of), so a re-issued task is cut
 // into the same sub-tiles no matter which other tasks share the launch.
-enum TileClass : int { kTileLarge = 0 /* 256 x 256 */, kTileSmall = 1 /* 128 x 128 */, kNumTileClasses = 2 };
+enum TileClass : int { kTileLarge = 0 /* 256 x 128 */, kTileSmall = 1 /* 128 x 128 */, kNumTileClasses = 2 };
 
-inline int tile_edge(int cls) { return cls == kTileLarge ? 256 : 128; }
+inline int tile_rows(int cls) { return cls == kTileLarge ? 256 : 128; }
+inline int tile_cols(int) { return 128; }
 
-inline int tile_class_of(const cleave_task& t) {
-  return (t.m_len > 128 && t.n_len > 128) ? kTileLarge : kTileSmall;
-}
+inline int tile_class_of(const cleave_task& t) { return t.m_len > 128 ? kTileLarge : kTileSmall; }
 
 // One unit of work of the execute kernel: a sub-tile of one task's output
 // block, computed over the task's whole chunk of the inner dimension.
 struct WorkItem {
   uint32_t task;    // index into the task table
   uint32_t sub;     // sub-tile index within the task's block, row-major over
-                    // ceil(m_len/edge) x ceil(n_len/edge) sub-tiles
+                    // ceil(m_len/tile_rows) x ceil(n_len/tile_cols) sub-tiles
 };
 static_assert(sizeof(WorkItem) == 8, "WorkItem is 8 bytes");
 
@@ -49,6 +48,7 @@ struct cleave_plan {
   int64_t num_tiles = 0;
   bool all_k_mult8 = true;   // every k0 and k_len is a multiple of 8
   bool all_k_mult4 = true;
+  bool all_klen_mult32 = true;  // every k_len is a multiple of 32
   bool all_mn_mult8 = true;  // every m0, m_len, n0, n_len is a multiple of 8
   bool all_mn_mult4 = true;
   bool all_n_mult4 = true;   // every n0, n_len multiple of 4 (vector path of reduce)
