@@ -145,9 +145,6 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
 
   int rc = ensure_uploaded(plan);
   if (rc != CLEAVE_OK) return rc;
-  int cus = 0;
-  rc = compute_units(&cus);
-  if (rc != CLEAVE_OK) return rc;
 
   // 16-byte load path: every chunk and tile edge a multiple of 16 bytes and
   // all rows of both operands starting on 16-byte boundaries.
@@ -204,10 +201,12 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
     args.transA = transA;
     args.transB = transB;
     args.partials = partials;
-    // Two resident workgroups per CU for the 256 x 128 tile (128 accumulator
-    // registers per lane, 54 KB of LDS each), four for the 128 x 128 tile.
-    const int64_t resident = static_cast<int64_t>(cus) * (c == cleave::kTileLarge ? 2 : 4);
-    const int grid = static_cast<int>(std::min<int64_t>(counts[c], resident));
+    // One workgroup per work item (the kernels loop only if the grid is
+    // capped): the hardware dispatcher then balances uneven items and keeps
+    // the workgroups that share a CU out of phase, so that one's partial-block
+    // stores overlap the other's MFMAs.
+    constexpr int64_t kMaxGrid = int64_t{1} << 20;
+    const int grid = static_cast<int>(std::min<int64_t>(counts[c], kMaxGrid));
     const bool direct = vec && dtype == CLEAVE_BF16 && c == cleave::kTileLarge && plan->all_klen_mult32;
     if (direct) {
       CLEAVE_HIP(cleave::launch_execute_direct(args, grid, stream));
