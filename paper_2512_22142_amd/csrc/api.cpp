@@ -245,7 +245,7 @@ extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, 
   args.partials = partials;
   args.C = C;
   args.ldc = ldc;
-  const int grid = static_cast<int>(std::min<int64_t>(args.n_items, static_cast<int64_t>(cus) * 16));
+  const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20)); (void)cus;
   CLEAVE_HIP(cleave::launch_reduce(args, out_dtype, vec, grid, stream));
   return CLEAVE_OK;
 }

@@ -31,6 +31,57 @@ __device__ __forceinline__ uint32_t to_bf16_bits(float x) {
   return u >> 16;
 }
 
+template <bool OUT_BF16>
+__device__ __forceinline__ void store4(void* C, int64_t off, f32x4 acc) {
+  if constexpr (OUT_BF16) {
+    u32x2 w;
+    w[0] = to_bf16_bits(acc[0]) | (to_bf16_bits(acc[1]) << 16);
+    w[1] = to_bf16_bits(acc[2]) | (to_bf16_bits(acc[3]) << 16);
+    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(C) + off) = w;
+  } else {
+    *reinterpret_cast<f32x4*>(static_cast<float*>(C) + off) = acc;
+  }
+}
+
+// Vector path for a compile-time split count: all S loads of two output
+// float4s are issued before the first add, so every thread keeps 2*S 16-byte
+// loads in flight.  The adds stay a left fold in ascending split order.
+template <bool OUT_BF16, int S>
+__device__ __forceinline__ void reduce_item_fixed(const float* p0, uint64_t block, uint32_t count,
+                                                  uint32_t n_len, void* C, int64_t c_base,
+                                                  int64_t ldc) {
+  constexpr uint32_t kStride = kThreads * 4;
+  uint32_t e = threadIdx.x * 4;
+  for (; e + kStride < count; e += 2 * kStride) {
+    f32x4 a[S], b[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      a[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p0 + s * block + e));
+      b[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p0 + s * block + e + kStride));
+    }
+    f32x4 acc0 = a[0], acc1 = b[0];
+#pragma unroll
+    for (int s = 1; s < S; ++s) {
+      acc0 = acc0 + a[s];
+      acc1 = acc1 + b[s];
+    }
+    const uint32_t r0 = e / n_len, r1 = (e + kStride) / n_len;
+    store4<OUT_BF16>(C, c_base + r0 * ldc + (e - r0 * n_len), acc0);
+    store4<OUT_BF16>(C, c_base + r1 * ldc + (e + kStride - r1 * n_len), acc1);
+  }
+  if (e < count) {
+    f32x4 a[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+      a[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p0 + s * block + e));
+    f32x4 acc = a[0];
+#pragma unroll
+    for (int s = 1; s < S; ++s) acc = acc + a[s];
+    const uint32_t r = e / n_len;
+    store4<OUT_BF16>(C, c_base + r * ldc + (e - r * n_len), acc);
+  }
+}
+
 template <bool OUT_BF16, bool VEC>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args) {
   for (int64_t it = blockIdx.x; it < args.n_items; it += gridDim.x) {
@@ -42,33 +93,29 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args) {
     const float* p0 = args.partials + task.partial_off + static_cast<uint64_t>(item.row0) * n_len;
     const uint32_t count = item.rows * n_len;
     const int64_t c_row0 = static_cast<int64_t>(task.m0) + item.row0;
+    const int64_t c_base = c_row0 * args.ldc + task.n0;
 
     if constexpr (VEC) {
-      for (uint32_t e = threadIdx.x * 4; e < count; e += kThreads * 4) {
-        f32x4 acc = *reinterpret_cast<const f32x4*>(p0 + e);
-        for (uint32_t s = 1; s < S; ++s) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(p0 + s * block + e);
-          acc = acc + v;
-        }
-        const uint32_t r = e / n_len;
-        const uint32_t c = e - r * n_len;
-        const int64_t off = (c_row0 + r) * args.ldc + task.n0 + c;
-        if constexpr (OUT_BF16) {
-          u32x2 w;
-          w[0] = to_bf16_bits(acc[0]) | (to_bf16_bits(acc[1]) << 16);
-          w[1] = to_bf16_bits(acc[2]) | (to_bf16_bits(acc[3]) << 16);
-          *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(args.C) + off) = w;
-        } else {
-          *reinterpret_cast<f32x4*>(static_cast<float*>(args.C) + off) = acc;
-        }
+      switch (S) {
+        case 1: reduce_item_fixed<OUT_BF16, 1>(p0, block, count, n_len, args.C, c_base, args.ldc); break;
+        case 2: reduce_item_fixed<OUT_BF16, 2>(p0, block, count, n_len, args.C, c_base, args.ldc); break;
+        case 4: reduce_item_fixed<OUT_BF16, 4>(p0, block, count, n_len, args.C, c_base, args.ldc); break;
+        case 8: reduce_item_fixed<OUT_BF16, 8>(p0, block, count, n_len, args.C, c_base, args.ldc); break;
+        default:
+          for (uint32_t e = threadIdx.x * 4; e < count; e += kThreads * 4) {
+            f32x4 acc = *reinterpret_cast<const f32x4*>(p0 + e);
+            for (uint32_t s = 1; s < S; ++s)
+              acc = acc + *reinterpret_cast<const f32x4*>(p0 + s * block + e);
+            const uint32_t r = e / n_len;
+            store4<OUT_BF16>(args.C, c_base + r * args.ldc + (e - r * n_len), acc);
+          }
       }
     } else {
       for (uint32_t e = threadIdx.x; e < count; e += kThreads) {
         float acc = p0[e];
         for (uint32_t s = 1; s < S; ++s) acc = acc + p0[s * block + e];
         const uint32_t r = e / n_len;
-        const uint32_t c = e - r * n_len;
-        const int64_t off = (c_row0 + r) * args.ldc + task.n0 + c;
+        const int64_t off = c_base + r * args.ldc + (e - r * n_len);
         if constexpr (OUT_BF16) {
           static_cast<uint16_t*>(args.C)[off] = static_cast<uint16_t>(to_bf16_bits(acc));
         } else {
