@@ -33,6 +33,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "kernels.h"
 #include "plan_internal.h"
@@ -72,6 +73,9 @@ constexpr int kLoadsPerStep = kLoadsA + kLoadsB;
 #define CLEAVE_WAIT_BARRIER(n) \
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(n) : "memory")
 
+template <int V>
+using int_c = std::integral_constant<int, V>;
+
 template <bool KCONTIG, int R>
 struct DirectTile {
   static constexpr int kLoads = R * kBK * 2 / 1024 / 4;
@@ -96,13 +100,23 @@ struct DirectTile {
   }
 
   // gbase: the tile's first row at this step's first k (wave-uniform);
-  // lds_tile: byte offset of the tile inside the workgroup's LDS.
-  __device__ __forceinline__ void issue(const unsigned char* gbase, unsigned char* lds_tile,
+  // lds_tile: LDS byte address of the tile.  The load is issued through inline
+  // asm (scalar base + per-lane 32-bit offset, LDS base in M0) for two
+  // reasons: no VALU address arithmetic in the K loop, and the compiler does
+  // not see an LDS-writing vector-memory operation -- it would otherwise wait
+  // for every load in flight before each LDS transpose read.  The statement
+  // has no register outputs, so nothing the compiler may spill or reuse is
+  // written asynchronously; completion is awaited with CLEAVE_WAIT_BARRIER.
+  __device__ __forceinline__ void issue(const unsigned char* gbase, uint32_t lds_tile,
                                         int wave) const {
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void)(gbase + goff[i]),
-                                       (lds_void)(lds_tile + (wave + 4 * i) * 1024), 16, 0, 0);
+    for (int i = 0; i < kLoads; ++i) {
+      const uint32_t lds = lds_tile + (wave + 4 * i) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(lds), "v"(goff[i]), "s"(gbase)
+                   : "memory");
+    }
   }
 };
 
@@ -117,14 +131,12 @@ __global__ __launch_bounds__(kNT, 2) void execute_direct_kernel(ExecuteArgs args
   const int wn = wave & 1;
   const int l32 = lane & 31;
   const int lh = lane >> 5;
-  // LDS reads per sub-step: one 16-byte read per K-contiguous block, two
-  // transpose reads per block otherwise.
-  constexpr int kReads = (A_K ? kMB : 2 * kMB) + (B_K ? kNB : 2 * kNB);
 
   // Lane-constant fragment addresses (byte offsets inside a stage).
   // K-contiguous: one per sub-step; blocks are 32 rows = 2048 bytes apart.
   // Transposed: one per block (the XOR touches the block bits); sub-step and
   // half select the k rows through a constant offset.
+  const uint32_t smem_off = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void)smem));
   const int i16 = lane & 15;
   const int kq = i16 >> 2;            // k row (mod 4) this lane addresses in a transpose read
   const int cq = i16 & 3;             // which 4 of the 16 columns
@@ -196,64 +208,42 @@ __global__ __launch_bounds__(kNT, 2) void execute_direct_kernel(ExecuteArgs args
 
     u32x4 fa[2][kMB], fb[2][kNB];
 
-    auto issue = [&](int s) {
-      unsigned char* stage = smem + (s % kStages) * kStage;
+    auto issue = [&](int s, int st) {
+      const uint32_t stage = smem_off + st * kStage;
       ta.issue(a_ptr + s * a_step, stage, wave);
       tb.issue(b_ptr + s * b_step, stage + kATile, wave);
     };
-    // Fragment reads are issued through inline asm so that the compiler does
-    // not order them against the in-flight direct loads (it would wait for all
-    // of those before every transpose read); their completion is awaited by
-    // frag_wait() below, which also ties the registers to the wait.
-    auto lds_off = [](const unsigned char* p) -> uint32_t {
-      return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void)p));
+    // Fragment reads are ordinary (compiler-visible) LDS loads: the compiler
+    // tracks their completion, and every address is a lane-constant register
+    // plus a compile-time offset (stage, block, sub-step).
+    auto tr_read = [&](const unsigned char* p) -> u32x2 {
+      return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)p));
     };
-    auto read_b128 = [&](uint32_t addr) -> u32x4 {
-      u32x4 v;
-      asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
-      return v;
-    };
-    auto read_tr = [&](uint32_t addr, uint32_t addr_hi) -> u32x4 {
-      u32x2 lo, hi;
-      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(addr_hi));
-      return u32x4{lo[0], lo[1], hi[0], hi[1]};
-    };
-    // Fragments of sub-step ks (0 or 1) of the stage into register set `buf`.
-    auto read_frags = [&](const unsigned char* stage, int ks, int buf) {
-      const uint32_t base = lds_off(stage);
+    // Fragments of sub-step KS (0 or 1) of ring stage ST into register set `buf`.
+    auto read_frags = [&](auto st, auto ks_tag, int buf) {
+      constexpr int ST = decltype(st)::value;
+      constexpr int KS = decltype(ks_tag)::value;
 #pragma unroll
       for (int i = 0; i < kMB; ++i) {
         if constexpr (A_K) {
-          fa[buf][i] = read_b128(base + a_addr[ks] + i * 2048);
+          fa[buf][i] = *reinterpret_cast<const u32x4*>(smem + a_addr[KS] + ST * kStage + i * 2048);
         } else {
-          const uint32_t p = base + a_addr[i] + ks * (16 * (kTM / 8) * 16);
-          fa[buf][i] = read_tr(p, p + 4 * (kTM / 8) * 16);
+          const unsigned char* p = smem + a_addr[i] + ST * kStage + KS * (16 * (kTM / 8) * 16);
+          const u32x2 lo = tr_read(p);
+          const u32x2 hi = tr_read(p + 4 * (kTM / 8) * 16);
+          fa[buf][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
         }
       }
 #pragma unroll
       for (int j = 0; j < kNB; ++j) {
         if constexpr (B_K) {
-          fb[buf][j] = read_b128(base + b_addr[ks] + j * 2048);
+          fb[buf][j] = *reinterpret_cast<const u32x4*>(smem + b_addr[KS] + ST * kStage + j * 2048);
         } else {
-          const uint32_t p = base + b_addr[j] + ks * (16 * (kTN / 8) * 16);
-          fb[buf][j] = read_tr(p, p + 4 * (kTN / 8) * 16);
+          const unsigned char* p = smem + b_addr[j] + ST * kStage + KS * (16 * (kTN / 8) * 16);
+          const u32x2 lo = tr_read(p);
+          const u32x2 hi = tr_read(p + 4 * (kTN / 8) * 16);
+          fb[buf][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
         }
-      }
-    };
-    // LDS reads return in order: once at most kReads (one sub-step's worth,
-    // issued after the set in question) are outstanding, set `buf` is complete.
-    // YOUNGER = true: a younger set has been issued since; false: none.
-    auto frag_wait = [&](int buf, bool younger) {
-      if (younger) {
-        asm volatile("s_waitcnt lgkmcnt(%6)"
-                     : "+v"(fa[buf][0]), "+v"(fa[buf][1]), "+v"(fa[buf][2]), "+v"(fa[buf][3]),
-                       "+v"(fb[buf][0]), "+v"(fb[buf][1])
-                     : "n"(kReads));
-      } else {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(fa[buf][0]), "+v"(fa[buf][1]), "+v"(fa[buf][2]), "+v"(fa[buf][3]),
-                       "+v"(fb[buf][0]), "+v"(fb[buf][1]));
       }
     };
     auto mma = [&](int buf) {
@@ -268,9 +258,9 @@ __global__ __launch_bounds__(kNT, 2) void execute_direct_kernel(ExecuteArgs args
 
     // Prologue.  The previous work item's last fragment reads completed before
     // its final barrier, so the ring can be refilled right away.
-    issue(0);
-    if (steps > 1) issue(1);
-    if (steps > 2) issue(2);
+    issue(0, 0);
+    if (steps > 1) issue(1, 1);
+    if (steps > 2) issue(2, 2);
     if (steps > 2) {
       CLEAVE_WAIT_BARRIER(2 * kLoadsPerStep);
     } else if (steps > 1) {
@@ -278,29 +268,34 @@ __global__ __launch_bounds__(kNT, 2) void execute_direct_kernel(ExecuteArgs args
     } else {
       CLEAVE_WAIT_BARRIER(0);
     }
-    read_frags(smem, 0, 0);
+    read_frags(int_c<0>{}, int_c<0>{}, 0);
 
-    for (int s = 0; s < steps; ++s) {
-      const unsigned char* cur = smem + (s % kStages) * kStage;
-      read_frags(cur, 1, 1);
-      frag_wait(0, true);
+    // One K step out of ring stage ST.  The barrier sits between the two
+    // sub-steps: by then this wave holds all fragments of step s, step s+1 has
+    // landed (loads return in order; only step s+2's may still be in flight),
+    // so stage ST can be refilled with step s+3 and the first fragments of step
+    // s+1 fetched while the second sub-step multiplies.
+    auto k_step = [&](auto st, int s) {
+      constexpr int ST = decltype(st)::value;
+      read_frags(st, int_c<1>{}, 1);
       mma(0);
-      // Step s+1 has landed (loads return in order; only step s+2's may still
-      // be in flight), and this wave's reads of stage s are complete.
       if (s + 2 < steps) {
         CLEAVE_WAIT_BARRIER(kLoadsPerStep);
       } else {
         CLEAVE_WAIT_BARRIER(0);
       }
-      if (s + 3 < steps) issue(s + 3);            // reuses the stage just read
-      if (s + 1 < steps) {
-        read_frags(smem + ((s + 1) % kStages) * kStage, 0, 0);
-        frag_wait(1, true);
-      } else {
-        frag_wait(1, false);
-      }
+      if (s + 3 < steps) issue(s + 3, ST);
+      if (s + 1 < steps) read_frags(int_c<(ST + 1) % kStages>{}, int_c<0>{}, 0);
       mma(1);
+    };
+    int s = 0;
+    for (; s + kStages <= steps; s += kStages) {
+      k_step(int_c<0>{}, s);
+      k_step(int_c<1>{}, s + 1);
+      k_step(int_c<2>{}, s + 2);
     }
+    if (s < steps) k_step(int_c<0>{}, s);
+    if (s + 1 < steps) k_step(int_c<1>{}, s + 1);
 
     // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
     // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
