@@ -82,22 +82,25 @@ int compute_units(int* out) {
 
 const char* kernel_name(int dtype, int cls, bool vec, int transA, int transB) {
   static const char* names[2][2][5] = {
-      {{"execute_f32_256x128_nn", "execute_f32_256x128_nt", "execute_f32_256x128_tn", "execute_f32_256x128_tt",
-        "execute_f32_256x128_scalar"},
+      {{"execute_f32_256x256_nn", "execute_f32_256x256_nt", "execute_f32_256x256_tn", "execute_f32_256x256_tt",
+        "execute_f32_256x256_scalar"},
        {"execute_f32_128x128_nn", "execute_f32_128x128_nt", "execute_f32_128x128_tn", "execute_f32_128x128_tt",
         "execute_f32_128x128_scalar"}},
-      {{"execute_bf16_256x128_nn", "execute_bf16_256x128_nt", "execute_bf16_256x128_tn", "execute_bf16_256x128_tt",
-        "execute_bf16_256x128_scalar"},
+      {{"execute_bf16_256x256_nn", "execute_bf16_256x256_nt", "execute_bf16_256x256_tn", "execute_bf16_256x256_tt",
+        "execute_bf16_256x256_scalar"},
        {"execute_bf16_128x128_nn", "execute_bf16_128x128_nt", "execute_bf16_128x128_tn", "execute_bf16_128x128_tt",
         "execute_bf16_128x128_scalar"}}};
   const int mode = vec ? (transA ? 2 : 0) + (transB ? 1 : 0) : 4;
   return names[dtype == CLEAVE_BF16 ? 1 : 0][cls][mode];
 }
 
-const char* direct_kernel_name(int transA, int transB) {
-  static const char* names[4] = {"execute_direct_bf16_256x128_nn", "execute_direct_bf16_256x128_nt",
-                                 "execute_direct_bf16_256x128_tn", "execute_direct_bf16_256x128_tt"};
-  return names[(transA ? 2 : 0) + (transB ? 1 : 0)];
+const char* direct_kernel_name(int cls, int transA, int transB) {
+  static const char* names[2][4] = {
+      {"execute_direct_bf16_256x256_nn", "execute_direct_bf16_256x256_nt",
+       "execute_direct_bf16_256x256_tn", "execute_direct_bf16_256x256_tt"},
+      {"execute_direct_bf16_128x128_nn", "execute_direct_bf16_128x128_nt",
+       "execute_direct_bf16_128x128_tn", "execute_direct_bf16_128x128_tt"}};
+  return names[cls][(transA ? 2 : 0) + (transB ? 1 : 0)];
 }
 
 }  // namespace
@@ -207,15 +210,16 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
     // stores overlap the other's MFMAs.
     constexpr int64_t kMaxGrid = int64_t{1} << 20;
     const int grid = static_cast<int>(std::min<int64_t>(counts[c], kMaxGrid));
-    const bool direct = vec && dtype == CLEAVE_BF16 && c == cleave::kTileLarge && plan->all_klen_mult32;
+    const bool direct = vec && dtype == CLEAVE_BF16 &&
+                        (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
     if (direct) {
-      CLEAVE_HIP(cleave::launch_execute_direct(args, grid, stream));
+      CLEAVE_HIP(cleave::launch_execute_direct(args, c, grid, stream));
     } else {
       CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
     }
     if (counts[c] > most) {
       most = counts[c];
-      plan->last_kernel = direct ? direct_kernel_name(transA, transB)
+      plan->last_kernel = direct ? direct_kernel_name(c, transA, transB)
                                  : kernel_name(dtype, c, vec, transA, transB);
     }
   }

@@ -192,7 +192,7 @@ struct OperandTile {
 // LDS refills and partial-block stores overlap with the other's MFMAs.
 // ---------------------------------------------------------------------------
 template <int EB, int TM, int TN, int WM, int WN, int MODE_A, int MODE_B>
-__global__ __launch_bounds__(WM* WN * 64, 2) void execute_kernel(ExecuteArgs args) {
+__global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_kernel(ExecuteArgs args) {
   constexpr int NT = WM * WN * 64;
   constexpr int E = 16 / EB;
   constexpr int kStepElems = kChunksPerRow * E;
@@ -408,10 +408,10 @@ hipError_t launch_modes(const ExecuteArgs& args, bool vec, int grid, hipStream_t
 hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
                           hipStream_t stream) {
   if (dtype == CLEAVE_BF16) {
-    return tile_class == kTileLarge ? launch_modes<2, 256, 128, 2, 2>(args, vec, grid, stream)
+    return tile_class == kTileLarge ? launch_modes<2, kLargeTileRows, kLargeTileCols, 2, kLargeTileCols / 64>(args, vec, grid, stream)
                                     : launch_modes<2, 128, 128, 2, 2>(args, vec, grid, stream);
   }
-  return tile_class == kTileLarge ? launch_modes<4, 256, 128, 2, 2>(args, vec, grid, stream)
+  return tile_class == kTileLarge ? launch_modes<4, kLargeTileRows, kLargeTileCols, 2, kLargeTileCols / 64>(args, vec, grid, stream)
                                   : launch_modes<4, 128, 128, 2, 2>(args, vec, grid, stream);
 }
 

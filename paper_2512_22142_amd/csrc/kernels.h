@@ -25,10 +25,13 @@ struct ExecuteArgs {
 hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
                           hipStream_t stream);
 
-// Enqueues the bf16 direct-to-LDS execute kernel (256 x 128 tiles).  The
+// Enqueues the bf16 direct-to-LDS execute kernel for one tile class.  The
 // caller has checked the 16-byte load conditions and that every chunk length
-// is a multiple of 32 elements.
-hipError_t launch_execute_direct(const ExecuteArgs& args, int grid, hipStream_t stream);
+// is a multiple of direct_k_step() elements.
+hipError_t launch_execute_direct(const ExecuteArgs& args, int tile_class, int grid,
+                                 hipStream_t stream);
+// Elements of K the direct kernel consumes per step: chunk lengths must be multiples of it.
+int direct_k_step();
 
 struct ReduceArgs {
   const cleave_task* tasks;

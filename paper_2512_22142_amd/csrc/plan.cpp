@@ -24,6 +24,78 @@ bool valid_split(int64_t K, int64_t S) {
   return (S - 1) * kc < K;
 }
 
+constexpr int kXcds = 8;
+
+void order_work_items(cleave_plan* p) {
+  // Region grid: minimise M/gm + N/gn over gm * gn = 8.
+  int gm = 1, gn = kXcds;
+  double best = 0.0;
+  for (int g = 1; g <= kXcds; g *= 2) {
+    const double cost = static_cast<double>(p->M) / g + static_cast<double>(p->N) / (kXcds / g);
+    if (g == 1 || cost < best) {
+      best = cost;
+      gm = g;
+      gn = kXcds / g;
+    }
+  }
+  std::vector<WorkItem> all[kNumTileClasses];
+  for (uint32_t i = 0; i < p->tasks.size(); ++i) append_work_items(p->tasks[i], i, all);
+  for (int cls = 0; cls < kNumTileClasses; ++cls) {
+    const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
+    const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
+    struct Key {
+      uint32_t split, m, n;
+      WorkItem item;
+    };
+    std::vector<Key> lists[kXcds];
+    for (const WorkItem& w : all[cls]) {
+      const cleave_task& t = p->tasks[w.task];
+      const uint32_t sub_cols = (t.n_len + tc - 1) / tc;
+      const uint32_t m = t.m0 + (w.sub / sub_cols) * tr;
+      const uint32_t n = t.n0 + (w.sub % sub_cols) * tc;
+      const int rm = static_cast<int>(static_cast<uint64_t>(m) * gm / static_cast<uint64_t>(p->M));
+      const int rn = static_cast<int>(static_cast<uint64_t>(n) * gn / static_cast<uint64_t>(p->N));
+      // relative position of the chunk inside [0, K): tiles with different
+      // split counts still line up by where in K they work
+      const uint32_t split = static_cast<uint32_t>(static_cast<uint64_t>(t.k0) * 64 / static_cast<uint64_t>(p->K));
+      lists[rm * gn + rn].push_back(Key{split, m, n, w});
+    }
+    size_t longest = 0;
+    for (auto& l : lists) {
+      std::stable_sort(l.begin(), l.end(), [](const Key& a, const Key& b) {
+        if (a.split != b.split) return a.split < b.split;
+        if (a.m != b.m) return a.m < b.m;
+        return a.n < b.n;
+      });
+      longest = std::max(longest, l.size());
+    }
+    // Interleave; when a region runs out, the slot is filled from the region
+    // that has most left, so the list has no holes.
+    size_t pos[kXcds] = {};
+    p->items[cls].reserve(all[cls].size());
+    for (size_t i = 0; i < longest; ++i) {
+      for (int x = 0; x < kXcds; ++x) {
+        int src = x;
+        if (pos[src] >= lists[src].size()) {
+          size_t most = 0;
+          src = -1;
+          for (int y = 0; y < kXcds; ++y) {
+            const size_t left = lists[y].size() - pos[y];
+            if (left > most) {
+              most = left;
+              src = y;
+            }
+          }
+          if (src < 0) break;
+        }
+        p->items[cls].push_back(lists[src][pos[src]++].item);
+      }
+    }
+    for (int x = 0; x < kXcds; ++x)
+      for (; pos[x] < lists[x].size(); ++pos[x]) p->items[cls].push_back(lists[x][pos[x]].item);
+  }
+}
+
 // Emits the task records of `tiles` in canonical order and fills the derived
 // tables.  Returns a status code.
 int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles, uint32_t gemm_id,
@@ -66,21 +138,21 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
       p->all_k_mult8 &= (k_or % 8 == 0);
       p->all_k_mult4 &= (k_or % 4 == 0);
       p->all_klen_mult32 &= (t.k_len % 32 == 0);
+      p->all_klen_mult64 &= (t.k_len % 64 == 0);
       p->all_mn_mult8 &= (mn_or % 8 == 0);
       p->all_mn_mult4 &= (mn_or % 4 == 0);
       p->all_n_mult4 &= ((t.n0 | t.n_len) % 4 == 0);
     }
 
     // Launch tables.  Execution order is free (only the task list's order is
-    // part of the interface): chunk index outermost, so that work items in
-    // flight at the same time read the same chunk of the inner dimension and
-    // share row panels of A / column panels of B in cache.
-    std::vector<uint32_t> order(p->tasks.size());
-    for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-      return p->tasks[a].ksplit_idx < p->tasks[b].ksplit_idx;
-    });
-    for (uint32_t idx : order) append_work_items(p->tasks[idx], idx, p->items);
+    // part of the interface).  Workgroups are dispatched round-robin over the
+    // 8 XCDs (workgroup b runs on XCD b % 8, each with its own L2), so work
+    // item 8*i + x is the i-th item of XCD x.  Every XCD gets a compact
+    // rectangle of the output (a gm x gn grid of regions with gm*gn = 8, chosen
+    // to minimise the operand panels a region needs), and walks it chunk index
+    // outermost: the items in flight on an XCD then share few row panels of A
+    // and column panels of B, at the same chunk of the inner dimension.
+    order_work_items(p);
 
     constexpr uint32_t kReduceElemsPerItem = 16384;
     for (uint32_t i = 0; i < p->tasks.size(); ++i) {

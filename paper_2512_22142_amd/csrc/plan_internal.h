@@ -12,12 +12,27 @@ namespace cleave {
 // Workgroup tile classes of the execute kernel.  Which class a task uses is a
 // pure function of its record (see tile_class_of), so a re-issued task is cut
 // into the same sub-tiles no matter which other tasks share the launch.
-enum TileClass : int { kTileLarge = 0 /* 256 x 128 */, kTileSmall = 1 /* 128 x 128 */, kNumTileClasses = 2 };
+enum TileClass : int { kTileLarge = 0, kTileSmall = 1, kNumTileClasses = 2 };
 
-inline int tile_rows(int cls) { return cls == kTileLarge ? 256 : 128; }
-inline int tile_cols(int) { return 128; }
+#ifndef CLEAVE_LARGE_TILE_ROWS
+#define CLEAVE_LARGE_TILE_ROWS 256
+#endif
+#ifndef CLEAVE_LARGE_TILE_COLS
+#define CLEAVE_LARGE_TILE_COLS 256
+#endif
+constexpr int kLargeTileRows = CLEAVE_LARGE_TILE_ROWS;
+constexpr int kLargeTileCols = CLEAVE_LARGE_TILE_COLS;
+constexpr int kSmallTileRows = 128;
+constexpr int kSmallTileCols = 128;
 
-inline int tile_class_of(const cleave_task& t) { return t.m_len > 128 ? kTileLarge : kTileSmall; }
+inline int tile_rows(int cls) { return cls == kTileLarge ? kLargeTileRows : kSmallTileRows; }
+inline int tile_cols(int cls) { return cls == kTileLarge ? kLargeTileCols : kSmallTileCols; }
+
+// Blocks with both edges above 128 are cut into large sub-tiles, everything
+// else into 128 x 128 ones.
+inline int tile_class_of(const cleave_task& t) {
+  return (t.m_len > 128 && t.n_len > 128) ? kTileLarge : kTileSmall;
+}
 
 // One unit of work of the execute kernel: a sub-tile of one task's output
 // block, computed over the task's whole chunk of the inner dimension.
@@ -49,6 +64,7 @@ struct cleave_plan {
   bool all_k_mult8 = true;   // every k0 and k_len is a multiple of 8
   bool all_k_mult4 = true;
   bool all_klen_mult32 = true;  // every k_len is a multiple of 32
+  bool all_klen_mult64 = true;
   bool all_mn_mult8 = true;  // every m0, m_len, n0, n_len is a multiple of 8
   bool all_mn_mult4 = true;
   bool all_n_mult4 = true;   // every n0, n_len multiple of 4 (vector path of reduce)
