@@ -340,7 +340,9 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 
     // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
     // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
-    // half a wave writes one aligned 128-byte run per store.
+    // half a wave writes one aligned 128-byte run per store.  The stores are
+    // non-temporal: a partial block is written once and read once, later, by
+    // the reducer.
     const int64_t ldp = task.n_len;
     const int row0 = wm * S::WTM + lh * 4;
     const int col0 = wn * S::WTN + l32;
@@ -355,7 +357,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
           for (int r = 0; r < 4; ++r) {
             float* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ldp;
 #pragma unroll
-            for (int j = 0; j < NB; ++j) p[j * 32] = acc[i][j][q * 4 + r];
+            for (int j = 0; j < NB; ++j) __builtin_nontemporal_store(acc[i][j][q * 4 + r], p + j * 32);
           }
     } else {
 #pragma unroll
@@ -368,7 +370,8 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
             float* p = tp + static_cast<int64_t>(rr) * ldp;
 #pragma unroll
             for (int j = 0; j < NB; ++j)
-              if (row0 + rr < m_valid && col0 + j * 32 < n_valid) p[j * 32] = acc[i][j][q * 4 + r];
+              if (row0 + rr < m_valid && col0 + j * 32 < n_valid)
+                __builtin_nontemporal_store(acc[i][j][q * 4 + r], p + j * 32);
           }
     }
   }
