@@ -204,17 +204,24 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
     args.transA = transA;
     args.transB = transB;
     args.partials = partials;
-    // One workgroup per work item (the kernels loop only if the grid is
-    // capped): the hardware dispatcher then balances uneven items and keeps
-    // the workgroups that share a CU out of phase, so that one's partial-block
-    // stores overlap the other's MFMAs.
-    constexpr int64_t kMaxGrid = int64_t{1} << 20;
-    const int grid = static_cast<int>(std::min<int64_t>(counts[c], kMaxGrid));
     const bool direct = vec && dtype == CLEAVE_BF16 &&
                         (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
     if (direct) {
+      // Persistent workgroups, as many as the chip holds at once: each walks
+      // the item list with the grid as stride and fetches the head of its next
+      // item while it stores the current one.
+      int cus = 0;
+      rc = compute_units(&cus);
+      if (rc != CLEAVE_OK) return rc;
+      const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(c);
+      const int grid = static_cast<int>(std::min<int64_t>(counts[c], resident));
       CLEAVE_HIP(cleave::launch_execute_direct(args, c, grid, stream));
     } else {
+      // One workgroup per work item (the kernel loops only if the grid is
+      // capped): the hardware dispatcher then balances uneven items and keeps
+      // the workgroups that share a CU out of phase.
+      constexpr int64_t kMaxGrid = int64_t{1} << 20;
+      const int grid = static_cast<int>(std::min<int64_t>(counts[c], kMaxGrid));
       CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
     }
     if (counts[c] > most) {

@@ -195,29 +195,70 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   const int64_t b_rs = args.transB ? args.ldb : 1;
   const int64_t b_ks = args.transB ? 1 : args.ldb;
 
-  for (int64_t it = blockIdx.x; it < args.n_items; it += gridDim.x) {
+  // Everything a work item needs, wave-uniform (scalar registers).
+  struct ItemCtx {
+    const unsigned char* a_ptr;   // first row of the A tile at the chunk's first k
+    const unsigned char* b_ptr;
+    float* out;                   // element (0, 0) of this sub-tile in the partial block
+    int64_t ldp;                  // row stride of the partial block
+    int steps, m_valid, n_valid;
+  };
+  auto load_ctx = [&](int64_t it) -> ItemCtx {
     const WorkItem item = args.items[it];
     const cleave_task task = args.tasks[item.task];
     const uint32_t sub_cols = (task.n_len + TN - 1) / TN;
     const uint32_t sub_m = item.sub / sub_cols;
     const uint32_t sub_n = item.sub - sub_m * sub_cols;
-    const int m_valid = min(static_cast<int>(task.m_len - sub_m * TM), TM);
-    const int n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
     const int64_t m_base = static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * TM;
     const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * TN;
-    const int steps = static_cast<int>(task.k_len) / S::BK;
+    ItemCtx c;
+    c.m_valid = min(static_cast<int>(task.m_len - sub_m * TM), TM);
+    c.n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
+    c.steps = static_cast<int>(task.k_len) / S::BK;
+    c.a_ptr = static_cast<const unsigned char*>(args.A) +
+              (m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * 2;
+    c.b_ptr = static_cast<const unsigned char*>(args.B) +
+              (n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
+    c.ldp = task.n_len;
+    c.out = args.partials + task.partial_off + static_cast<int64_t>(sub_m) * TM * c.ldp + sub_n * TN;
+    return c;
+  };
+  const int64_t a_step = a_ks * S::BK * 2;    // bytes per K step
+  const int64_t b_step = b_ks * S::BK * 2;
 
-    const unsigned char* a_ptr = static_cast<const unsigned char*>(args.A) +
-                                 (m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * 2;
-    const unsigned char* b_ptr = static_cast<const unsigned char*>(args.B) +
-                                 (n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
-    const int64_t a_step = a_ks * S::BK * 2;    // bytes per K step
-    const int64_t b_step = b_ks * S::BK * 2;
+  DirectTile<S, A_K, TM> ta;
+  DirectTile<S, B_K, TN> tb;
+  auto issue = [&](const ItemCtx& c, int s, int st) {
+    const uint32_t stage = smem_off + st * kStage;
+    ta.issue(c.a_ptr + s * a_step, stage, wave);
+    tb.issue(c.b_ptr + s * b_step, stage + kATile, wave);
+  };
+  // Start of a work item: lane offsets for its (possibly clipped) tile, then
+  // the first STAGES steps into the ring.
+  auto fill_ring = [&](const ItemCtx& c) {
+    ta.init(a_rs, a_ks, c.m_valid, wave, lane);
+    tb.init(b_rs, b_ks, c.n_valid, wave, lane);
+#pragma unroll
+    for (int st = 0; st < STAGES; ++st)
+      if (st < c.steps) issue(c, st, st);
+  };
 
-    DirectTile<S, A_K, TM> ta;
-    DirectTile<S, B_K, TN> tb;
-    ta.init(a_rs, a_ks, m_valid, wave, lane);
-    tb.init(b_rs, b_ks, n_valid, wave, lane);
+  int64_t it = blockIdx.x;
+  if (it >= args.n_items) return;
+  ItemCtx c = load_ctx(it);
+  fill_ring(c);
+  // True when this item's ring fill was followed by the previous item's full
+  // epilogue: more stores than the vector-memory counter can hold (63) were
+  // issued after those loads, and the counter retires in issue order, so the
+  // loads have landed once the stores have all been issued.
+  bool fill_landed = false;
+
+  for (;;) {
+    const int64_t it_next = it + gridDim.x;
+    const bool has_next = it_next < args.n_items;
+    ItemCtx nx = c;
+    if (has_next) nx = load_ctx(it_next);
+    const int steps = c.steps;
 
     f32x16 acc[MB][NB];
 #pragma unroll
@@ -229,11 +270,6 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 
     u32x4 fa[2][MB], fb[2][NB];
 
-    auto issue = [&](int s, int st) {
-      const uint32_t stage = smem_off + st * kStage;
-      ta.issue(a_ptr + s * a_step, stage, wave);
-      tb.issue(b_ptr + s * b_step, stage + kATile, wave);
-    };
     // Fragment reads are ordinary (compiler-visible) LDS loads: the compiler
     // tracks their completion, and every address is a lane-constant register
     // plus a compile-time offset (stage, block, sub-step).
@@ -279,12 +315,11 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
               acc[i][j], 0, 0, 0);
     };
 
-    // Prologue: fill the ring.  The previous work item's last fragment reads
-    // completed before its final barrier, so the stages are free.
-#pragma unroll
-    for (int st = 0; st < STAGES; ++st)
-      if (st < steps) issue(st, st);
-    if (steps >= STAGES) {
+    // Step 0 must have landed.  All earlier fragment reads of this workgroup
+    // completed before the previous item's final barrier.
+    if (fill_landed) {
+      CLEAVE_WAIT_BARRIER(63);
+    } else if (steps >= STAGES) {
       CLEAVE_WAIT_BARRIER((STAGES - 1) * LPS);
     } else {
       CLEAVE_WAIT_BARRIER(0);
@@ -310,12 +345,16 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         sub(int_c<1>{});
         sub(int_c<2>{});
       }
-      if (s + STAGES - 1 < steps) {
+      if (fill_landed && s + 1 < STAGES) {
+        // step s+1 belongs to the ring fill: nothing to wait for, and no reason
+        // to wait for the previous item's stores either
+        CLEAVE_WAIT_BARRIER(63);
+      } else if (s + STAGES - 1 < steps) {
         CLEAVE_WAIT_BARRIER((STAGES - 2) * LPS);
       } else {
         CLEAVE_WAIT_BARRIER(0);
       }
-      if (s + STAGES < steps) issue(s + STAGES, ST);
+      if (s + STAGES < steps) issue(c, s + STAGES, ST);
       if (s + 1 < steps) read_frags(int_c<(ST + 1) % STAGES>{}, int_c<0>{}, 0);
       mma((kSub - 1) & 1);
     };
@@ -338,17 +377,23 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       if (s + 3 < steps) k_step(int_c<3>{}, s + 3);
     }
 
+    // Every wave is past the last step's barrier, hence past all of its
+    // fragment reads: the ring is free.  The next item's ring fill is issued
+    // before this item's stores so that its latency hides behind them.
+    const int row0 = wm * S::WTM + lh * 4;
+    const int col0 = wn * S::WTN + l32;
+    const int64_t ldp = c.ldp;
+    float* tp = c.out + row0 * ldp + col0;
+    const int m_valid = c.m_valid, n_valid = c.n_valid;
+    const bool interior = m_valid == TM && n_valid == TN;
+    if (has_next) fill_ring(nx);
+
     // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
     // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
     // half a wave writes one aligned 128-byte run per store.  The stores are
     // non-temporal: a partial block is written once and read once, later, by
     // the reducer.
-    const int64_t ldp = task.n_len;
-    const int row0 = wm * S::WTM + lh * 4;
-    const int col0 = wn * S::WTN + l32;
-    float* tp = args.partials + task.partial_off +
-                (static_cast<int64_t>(sub_m) * TM + row0) * ldp + sub_n * TN + col0;
-    if (m_valid == TM && n_valid == TN) {
+    if (interior) {
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -374,6 +419,11 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
                 __builtin_nontemporal_store(acc[i][j][q * 4 + r], p + j * 32);
           }
     }
+    if (!has_next) break;
+    static_assert(MB * NB * 16 >= 63, "a full epilogue must saturate the vector-memory counter");
+    fill_landed = interior;
+    c = nx;
+    it = it_next;
   }
 }
 
@@ -403,7 +453,10 @@ hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
 #define CLEAVE_DIRECT_SHAPE_LARGE Shape<kLargeTileRows, kLargeTileCols, 2, 4, 64, 2, 1>
 #endif
 using LargeShape = CLEAVE_DIRECT_SHAPE_LARGE;
-using SmallShape = Shape<kSmallTileRows, kSmallTileCols, 2, 2, 64, 2, 2>;
+#ifndef CLEAVE_DIRECT_SHAPE_SMALL
+#define CLEAVE_DIRECT_SHAPE_SMALL Shape<kSmallTileRows, kSmallTileCols, 2, 2, 64, 2, 2>
+#endif
+using SmallShape = CLEAVE_DIRECT_SHAPE_SMALL;
 static_assert(LargeShape::TM == kLargeTileRows && LargeShape::TN == kLargeTileCols,
               "the kernel's tile must be the host's sub-tile of the large class");
 static_assert(LargeShape::BK == SmallShape::BK, "one K step for both classes");
@@ -421,6 +474,10 @@ hipError_t launch_layouts(const ExecuteArgs& args, int grid, hipStream_t stream)
 }  // namespace
 
 int direct_k_step() { return LargeShape::BK; }
+
+int direct_workgroups_per_cu(int tile_class) {
+  return tile_class == kTileLarge ? LargeShape::WGS : SmallShape::WGS;
+}
 
 hipError_t launch_execute_direct(const ExecuteArgs& args, int tile_class, int grid,
                                  hipStream_t stream) {

@@ -30,6 +30,8 @@ hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bo
 // is a multiple of direct_k_step() elements.
 hipError_t launch_execute_direct(const ExecuteArgs& args, int tile_class, int grid,
                                  hipStream_t stream);
+// Workgroups of the direct kernel that one CU holds at a time, per tile class.
+int direct_workgroups_per_cu(int tile_class);
 // Elements of K the direct kernel consumes per step: chunk lengths must be multiples of it.
 int direct_k_step();
 
