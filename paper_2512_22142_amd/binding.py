@@ -52,6 +52,11 @@ def _load():
         raise ImportError(
             "libcleave.so is not built: run `python -m paper_2512_22142_amd.build` "
             "(or __graft_entry__.build()) first")
+    # Device pointers and streams come from PyTorch, so the library must bind to
+    # the HIP runtime instance PyTorch has loaded: import torch first, whatever
+    # order the caller imports things in (two runtimes in one process do not see
+    # each other's devices or allocations).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     i64, i32, u32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p
     lib.cleave_plan_uniform.argtypes = [i64, i64, i64, i64, i64, i32, u32, ctypes.POINTER(p)]

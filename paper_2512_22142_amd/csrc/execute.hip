@@ -355,7 +355,7 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
           for (int r = 0; r < 4; ++r) {
             float* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ldp;
 #pragma unroll
-            for (int j = 0; j < NB; ++j) __builtin_nontemporal_store(acc[i][j][q * 4 + r], p + j * 32);
+            for (int j = 0; j < NB; ++j) p[j * 32] = acc[i][j][q * 4 + r];
           }
     } else {
 #pragma unroll
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
 #pragma unroll
             for (int j = 0; j < NB; ++j)
               if (row0 + rr < m_valid && col0 + j * 32 < n_valid)
-                __builtin_nontemporal_store(acc[i][j][q * 4 + r], p + j * 32);
+                p[j * 32] = acc[i][j][q * 4 + r];
           }
     }
   }
