@@ -25,6 +25,29 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBPS = 8000.0
 
+# HBM-side bytes per launch (average over the 21 launches of a c3 step) from the
+# FETCH_SIZE and WRITE_SIZE counter runs summarised under profiles/ (FETCH_SIZE
+# scaled by 2.0, WRITE_SIZE by 1.0: what the same counters read for a plain copy
+# of known size).  Valid only for the kernel sources they were taken with: the
+# digest below is checked at run time and the figures are dropped on a mismatch.
+COUNTER_TRAFFIC = {
+    "workload": "c3",
+    "sources_sha256": "290eb68c76dc8e29235d55ed45c460ce7672d0fe4abda30591fbb36ede67dcf6",
+    "execute_bytes_per_launch": (2.0 * 276394 + 396349) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194451 + 97134) * 1024,
+}
+
+
+def kernel_sources_digest():
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2512_22142_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -139,6 +162,10 @@ def main():
     red_gbps = sum(red_bytes) / (red_total_ms * 1e-3) / 1e9
     value = total_flops / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    counters_valid = (args.config == COUNTER_TRAFFIC["workload"] and
+                      kernel_sources_digest() == COUNTER_TRAFFIC["sources_sha256"])
+    exec_traffic = round(COUNTER_TRAFFIC["execute_bytes_per_launch"]) if counters_valid else None
+    red_traffic = round(COUNTER_TRAFFIC["reduce_bytes_per_launch"]) if counters_valid else None
 
     per_gemm = [{"gemm": g.name, "tasks": plan.num_tasks, "kernel": plan.last_kernel,
                  "execute_ms": round(exec_ms[i], 4), "execute_tflops": round(flops[i] / exec_ms[i] / 1e9, 1),
@@ -174,7 +201,11 @@ def main():
         "roofline": {
             "kernel": "execute", "bound": "mfma",
             "achieved": round(exec_tflops, 2), "peak": peak, "unit": "TFLOP/s",
-            "frac": round(exec_tflops / peak, 4), "traffic": None,
+            "frac": round(exec_tflops / peak, 4), "traffic": exec_traffic,
+            "traffic_unit": "HBM-side bytes per launch (counters)",
+            "algorithmic_bytes_per_launch_avg": sum(
+                (g.M * g.K + g.K * g.N) * in_bytes + plan.partial_elems * 4
+                for g, plan, _, _ in gemms) / len(gemms),
             "launches_per_step": len(gemms),
             "avg_launch_ms": round(exec_total_ms / len(gemms), 4),
             "flops_per_launch_avg": total_flops / len(gemms),
@@ -182,7 +213,7 @@ def main():
         "reduce_roofline": {
             "kernel": "reduce", "bound": "hbm",
             "achieved": round(red_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-            "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+            "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": red_traffic,
             "avg_launch_ms": round(red_total_ms / len(gemms), 4),
             "bytes_per_launch_avg": sum(red_bytes) / len(gemms),
         },

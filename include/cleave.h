@@ -91,7 +91,8 @@ typedef struct cleave_plan cleave_plan; /* opaque, host-owned */
  * column of tiles clipped (never padded).  All arguments host values; *out is
  * a new plan the caller destroys with cleave_plan_destroy.
  * CLEAVE_EINVAL: a non-positive size, a dimension above 2^31-1, an empty
- * chunk, out == NULL. */
+ * chunk, out == NULL, or a plan whose 32-bit indices would wrap (more than
+ * 2^32-1 tasks, or a single tile of more than 2^32-1 128 x 128 sub-tiles). */
 int cleave_plan_uniform(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
                         int32_t ksplit, uint32_t gemm_id, cleave_plan** out);
 

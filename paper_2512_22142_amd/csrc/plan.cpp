@@ -109,6 +109,24 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
     p->num_tiles = static_cast<int64_t>(tiles.size());
     uint64_t off = 0;
     uint32_t tile_id = 0;
+    // Task, tile and sub-tile indices are 32-bit in the task record and the
+    // launch tables, offsets 64-bit: refuse a plan that does not fit rather
+    // than wrap.
+    constexpr uint64_t kMaxIndex = std::numeric_limits<uint32_t>::max();
+    constexpr uint64_t kMaxElems = static_cast<uint64_t>(std::numeric_limits<int64_t>::max()) / 8;
+    uint64_t n_tasks = 0;
+    for (const Tile& tl : tiles) {
+      n_tasks += static_cast<uint64_t>(tl.ksplit);
+      const uint64_t subs = static_cast<uint64_t>((tl.m_len + kSmallTileRows - 1) / kSmallTileRows) *
+                            static_cast<uint64_t>((tl.n_len + kSmallTileCols - 1) / kSmallTileCols);
+      const uint64_t elems = static_cast<uint64_t>(tl.m_len) * static_cast<uint64_t>(tl.n_len);
+      if (subs > kMaxIndex || n_tasks > kMaxIndex || elems > kMaxElems / static_cast<uint64_t>(tl.ksplit) ||
+          (off += elems * static_cast<uint64_t>(tl.ksplit)) > kMaxElems) {
+        delete p;
+        return CLEAVE_EINVAL;
+      }
+    }
+    off = 0;
     for (const Tile& tl : tiles) {
       const int64_t S = tl.ksplit;
       const int64_t kc = (K + S - 1) / S;

@@ -100,6 +100,13 @@ def test_explicit_plan_rejects_bad_lists(band_h, col_w, ks):
         planner.plan_explicit(8, 8, 8, band_h, col_w, ks)
 
 
+def test_plan_whose_indices_would_wrap_is_rejected():
+    big = 2**31 - 1
+    with pytest.raises(cleave.CleaveError) as e:
+        cleave.plan_uniform(big, big, 64, big, big, 1)   # one tile of 2^48 sub-tiles
+    assert e.value.status == -1
+
+
 def test_null_arguments_are_errors_not_crashes():
     lib = ctypes.CDLL(cleave.LIB_PATH)
     lib.cleave_plan_uniform.argtypes = [ctypes.c_int64] * 5 + [ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p]
