@@ -6,5 +6,5 @@ set of re-issued tasks).  Both the oracle and the HIP library receive these
 values as plain inputs.
 """
 from .configs import GemmSpec, LayerConfig, layer_config, CONFIG_NAMES  # noqa: F401
-from .tensors import make_tensor, make_gemm_operands  # noqa: F401
+from .tensors import make_tensor, make_gemm_operands, make_probe_vectors  # noqa: F401
 from .hetero import draw_explicit_tiling, draw_reissue  # noqa: F401

@@ -50,3 +50,17 @@ def make_matrix(seed, rows, cols, dtype="bf16", std=1.0, integer_valued=False):
     else:
         t = torch.randn((rows, cols), generator=g, dtype=torch.float32) * std
     return t.to(_DTYPES[dtype])
+
+
+def make_probe_vectors(seed, M, N, kind="normal"):
+    """Seeded fp32 probe vectors r (M entries) and s (N entries) for the
+    returned-block check: standard normal, or +-1 with equal probability."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    if kind == "normal":
+        return (torch.randn(M, generator=g, dtype=torch.float32),
+                torch.randn(N, generator=g, dtype=torch.float32))
+    if kind == "sign":
+        return (torch.randint(0, 2, (M,), generator=g, dtype=torch.int32).to(torch.float32) * 2 - 1,
+                torch.randint(0, 2, (N,), generator=g, dtype=torch.int32).to(torch.float32) * 2 - 1)
+    raise ValueError(kind)
