@@ -145,6 +145,35 @@ int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
 int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
                   int out_dtype, void* hip_stream);
 
+/* ---- verify --------------------------------------------------------------
+ * Check of returned partial blocks by random projection (paper Sec. 6,
+ * "Robustness to poisoning attacks": r^T (A B) s = (A^T r)^T (B s), matrix-
+ * vector work only).  For every task t of the plan, with A_blk = op(A)[m0:m0+
+ * m_len, k0:k0+k_len], B_blk = op(B)[k0:k0+k_len, n0:n0+n_len], P_t the task's
+ * block in `partials`, r_t = r[m0:m0+m_len] and s_t = s[n0:n0+n_len]:
+ *     lhs[t]   = r_t^T P_t s_t
+ *     rhs[t]   = (A_blk^T r_t)^T (B_blk s_t)
+ *     scale[t] = (|A_blk|^T |r_t|)^T (|B_blk| |s_t|)
+ *     accept[t] = 1 if |lhs[t] - rhs[t]| <= tol * scale[t], else 0
+ * all sums carried in fp64 in a fixed order (exact, hence lhs == rhs for a
+ * correct block, when all values are small integers).
+ * A, B, lda, ldb, transA, transB, dtype, partials: as for cleave_execute (the
+ * call only reads them).  r: device, M floats; s: device, N floats -- the
+ * caller draws them afresh per check.  tol >= 0 (host value).  lhs, rhs,
+ * scale: device, num_tasks doubles each, any of them may be NULL; accept:
+ * device, num_tasks int32, required.  Asynchronous on hip_stream.  The first
+ * call on a plan allocates device scratch owned by the plan (projections of
+ * the operands per distinct row / column range of the tiling, per-item sums);
+ * two verify calls on one plan must not overlap in time.
+ * CLEAVE_EINVAL: NULL or misaligned pointer, bad enum, short leading
+ * dimension, negative or NaN tol. */
+int cleave_verify(cleave_plan* plan,
+                  const void* A, int64_t lda, int transA,
+                  const void* B, int64_t ldb, int transB, int dtype,
+                  const float* partials, const float* r, const float* s, double tol,
+                  double* lhs, double* rhs, double* scale, int32_t* accept,
+                  void* hip_stream);
+
 /* ---- misc ----------------------------------------------------------------*/
 const char* cleave_strerror(int status);
 /* hipError_t value of the most recent CLEAVE_EHIP on this thread (0 if none). */

@@ -34,7 +34,7 @@ EXPORTS = (
     "cleave_plan_num_tiles", "cleave_plan_tasks", "cleave_plan_partial_elems",
     "cleave_plan_dims", "cleave_plan_upload", "cleave_plan_destroy", "cleave_execute",
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
-    "cleave_plan_last_kernel",
+    "cleave_plan_last_kernel", "cleave_verify",
 )
 
 
@@ -78,6 +78,9 @@ def _load():
                                    ctypes.c_int, p, p]
     lib.cleave_execute.restype = ctypes.c_int
     lib.cleave_reduce.argtypes = [p, p, p, i64, ctypes.c_int, p]
+    lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
+                                  p, p, p, ctypes.c_double, p, p, p, p, p]
+    lib.cleave_verify.restype = ctypes.c_int
     lib.cleave_reduce.restype = ctypes.c_int
     lib.cleave_strerror.argtypes = [ctypes.c_int]
     lib.cleave_strerror.restype = ctypes.c_char_p
@@ -216,6 +219,38 @@ def reduce(plan, partials, C, stream=None):
         raise ValueError("C must be M x N")
     _check(_lib.cleave_reduce(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
                               _dtype_code(C), _stream_ptr(stream)), "cleave_reduce")
+
+
+def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=None,
+           transA=0, transB=0, stream=None):
+    """cleave_verify: r (M) and s (N) fp32 device vectors, accept an int32 device
+    tensor of num_tasks entries; lhs / rhs / scale optional fp64 device tensors
+    of num_tasks entries.  Nothing is allocated or computed here."""
+    import torch
+    a_ptr, lda = _matrix(A, "A")
+    b_ptr, ldb = _matrix(B, "B")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    a_rows, a_cols = (plan.K, plan.M) if transA else (plan.M, plan.K)
+    b_rows, b_cols = (plan.N, plan.K) if transB else (plan.K, plan.N)
+    if tuple(A.shape) != (a_rows, a_cols) or tuple(B.shape) != (b_rows, b_cols):
+        raise ValueError("operand shapes %s, %s do not match the plan" % (tuple(A.shape), tuple(B.shape)))
+
+    def vec(t, dtype, n, what, optional=False):
+        if t is None and optional:
+            return None
+        if t is None or t.dtype != dtype or not t.is_cuda or not t.is_contiguous() or t.numel() < n:
+            raise ValueError("%s must be a contiguous %s device tensor of at least %d entries" % (what, dtype, n))
+        return ctypes.c_void_p(t.data_ptr())
+
+    _check(_lib.cleave_verify(
+        plan._h, a_ptr, lda, int(transA), b_ptr, ldb, int(transB), _dtype_code(A),
+        vec(partials, torch.float32, plan.partial_elems, "partials"),
+        vec(r, torch.float32, plan.M, "r"), vec(s, torch.float32, plan.N, "s"), float(tol),
+        vec(lhs, torch.float64, plan.num_tasks, "lhs", True),
+        vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
+        vec(scale, torch.float64, plan.num_tasks, "scale", True),
+        vec(accept, torch.int32, plan.num_tasks, "accept"), _stream_ptr(stream)), "cleave_verify")
 
 
 def version():

@@ -3,7 +3,10 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <limits>
+#include <map>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "kernels.h"
@@ -26,7 +29,20 @@ int hip_fail(hipError_t e) {
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+void free_verify_device(cleave::VerifyTables* v) {
+  if (!v) return;
+  void* ptrs[] = {v->d_row_segs, v->d_col_segs, v->d_task_row_seg, v->d_task_col_seg,
+                  v->d_items, v->d_task_first_item, v->d_proj, v->d_item_sums};
+  for (void* q : ptrs)
+    if (q) (void)hipFree(q);
+  v->d_row_segs = v->d_col_segs = nullptr;
+  v->d_task_row_seg = v->d_task_col_seg = v->d_task_first_item = nullptr;
+  v->d_items = nullptr;
+  v->d_proj = v->d_item_sums = nullptr;
+}
+
 void free_device_tables(cleave_plan* p) {
+  free_verify_device(p->verify);
   if (p->d_tasks) (void)hipFree(p->d_tasks);
   for (int c = 0; c < cleave::kNumTileClasses; ++c)
     if (p->d_items[c]) (void)hipFree(p->d_items[c]);
@@ -115,6 +131,7 @@ extern "C" int cleave_plan_upload(cleave_plan* plan) {
 extern "C" void cleave_plan_destroy(cleave_plan* plan) {
   if (!plan) return;
   if (plan->device >= 0) free_device_tables(plan);
+  delete plan->verify;
   delete plan;
 }
 
@@ -258,5 +275,128 @@ extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, 
   args.ldc = ldc;
   const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20)); (void)cus;
   CLEAVE_HIP(cleave::launch_reduce(args, out_dtype, vec, grid, stream));
+  return CLEAVE_OK;
+}
+
+namespace {
+
+// Host tables of the returned-block check (built once per plan) and their
+// device copies plus scratch (once per device the plan is used on).
+int ensure_verify_tables(cleave_plan* p) {
+  using cleave::Segment;
+  using cleave::VerifyItem;
+  if (!p->verify) {
+    cleave::VerifyTables* v = new (std::nothrow) cleave::VerifyTables;
+    if (!v) return CLEAVE_ENOMEM;
+    try {
+      std::map<std::pair<uint32_t, uint32_t>, uint32_t> rows, cols;
+      constexpr uint32_t kElemsPerItem = 65536;
+      v->task_first_item.push_back(0);
+      for (const cleave_task& t : p->tasks) {
+        auto ri = rows.emplace(std::make_pair(t.m0, t.m_len), static_cast<uint32_t>(rows.size()));
+        if (ri.second) v->row_segs.push_back(Segment{t.m0, t.m_len});
+        v->task_row_seg.push_back(ri.first->second);
+        auto ci = cols.emplace(std::make_pair(t.n0, t.n_len), static_cast<uint32_t>(cols.size()));
+        if (ci.second) v->col_segs.push_back(Segment{t.n0, t.n_len});
+        v->task_col_seg.push_back(ci.first->second);
+        const uint32_t rows_per = std::max<uint32_t>(1, kElemsPerItem / t.n_len);
+        const uint32_t index = static_cast<uint32_t>(&t - p->tasks.data());
+        for (uint32_t r0 = 0; r0 < t.m_len; r0 += rows_per)
+          v->items.push_back(VerifyItem{index, r0, std::min(rows_per, t.m_len - r0), 0});
+        if (v->items.size() > std::numeric_limits<uint32_t>::max()) {
+          delete v;
+          return CLEAVE_EINVAL;
+        }
+        v->task_first_item.push_back(static_cast<uint32_t>(v->items.size()));
+      }
+      for (const std::vector<Segment>* segs : {&v->row_segs, &v->col_segs})
+        for (const Segment& sg : *segs) {
+          v->segs_mult8 &= ((sg.start | sg.len) % 8 == 0);
+          v->segs_mult4 &= ((sg.start | sg.len) % 4 == 0);
+        }
+    } catch (const std::bad_alloc&) {
+      delete v;
+      return CLEAVE_ENOMEM;
+    }
+    p->verify = v;
+  }
+  cleave::VerifyTables* v = p->verify;
+  if (v->d_items || p->tasks.empty()) return CLEAVE_OK;
+  int rc = upload_vector(v->row_segs, &v->d_row_segs);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->col_segs, &v->d_col_segs);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->task_row_seg, &v->d_task_row_seg);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->task_col_seg, &v->d_task_col_seg);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->task_first_item, &v->d_task_first_item);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->items, &v->d_items);
+  if (rc == CLEAVE_OK) {
+    const size_t proj = 2 * (v->row_segs.size() + v->col_segs.size()) * static_cast<size_t>(p->K);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&v->d_proj), proj * sizeof(double));
+    if (e == hipSuccess)
+      e = hipMalloc(reinterpret_cast<void**>(&v->d_item_sums), v->items.size() * sizeof(double));
+    if (e == hipErrorOutOfMemory) rc = CLEAVE_ENOMEM;
+    else if (e != hipSuccess) rc = hip_fail(e);
+  }
+  if (rc != CLEAVE_OK) free_verify_device(v);
+  return rc;
+}
+
+}  // namespace
+
+extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int transA,
+                             const void* B, int64_t ldb, int transB, int dtype,
+                             const float* partials, const float* r, const float* s, double tol,
+                             double* lhs, double* rhs, double* scale, int32_t* accept,
+                             void* hip_stream) {
+  if (!plan || !A || !B || !partials || !r || !s || !accept) return CLEAVE_EINVAL;
+  if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
+  if (lda < (transA ? plan->M : plan->K) || ldb < (transB ? plan->K : plan->N)) return CLEAVE_EINVAL;
+  if (!(tol >= 0.0)) return CLEAVE_EINVAL;   // also refuses NaN
+  const int eb = dtype == CLEAVE_BF16 ? 2 : 4;
+  if (!aligned(A, eb) || !aligned(B, eb) || !aligned(partials, 4) || !aligned(r, 4) ||
+      !aligned(s, 4) || !aligned(accept, 4) || !aligned(lhs, 8) || !aligned(rhs, 8) ||
+      !aligned(scale, 8))
+    return CLEAVE_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  int rc = ensure_uploaded(plan);
+  if (rc != CLEAVE_OK) return rc;
+  rc = ensure_verify_tables(plan);
+  if (rc != CLEAVE_OK) return rc;
+  cleave::VerifyTables* v = plan->verify;
+  if (plan->tasks.empty()) return CLEAVE_OK;
+
+  const int64_t K = plan->K;
+  const int e = 16 / eb;   // elements per 16-byte load
+  const bool segs_ok = e == 8 ? v->segs_mult8 : v->segs_mult4;
+  double* U = v->d_proj;
+  double* U_abs = U + v->row_segs.size() * static_cast<size_t>(K);
+  double* V = U_abs + v->row_segs.size() * static_cast<size_t>(K);
+  double* V_abs = V + v->col_segs.size() * static_cast<size_t>(K);
+
+  // op(A)[i][k]: stored M x K (transA = 0) -> the summed row index strides;
+  // stored K x M (transA = 1) -> it is contiguous.
+  cleave::ProjectArgs pa{A, lda, v->d_row_segs, static_cast<int>(v->row_segs.size()), r, U, U_abs, K};
+  const bool a_contig = transA != 0;
+  const bool a_vec = aligned(A, 16) && lda % e == 0 &&
+                     (a_contig ? (segs_ok && aligned(r, 16)) : K % e == 0);
+  CLEAVE_HIP(cleave::launch_project(pa, dtype, a_contig, a_vec, stream));
+  // op(B)[k][j]: stored K x N (transB = 0) -> the summed column index is
+  // contiguous; stored N x K (transB = 1) -> it strides.
+  cleave::ProjectArgs pb{B, ldb, v->d_col_segs, static_cast<int>(v->col_segs.size()), s, V, V_abs, K};
+  const bool b_contig = transB == 0;
+  const bool b_vec = aligned(B, 16) && ldb % e == 0 &&
+                     (b_contig ? (segs_ok && aligned(s, 16)) : K % e == 0);
+  CLEAVE_HIP(cleave::launch_project(pb, dtype, b_contig, b_vec, stream));
+
+  cleave::BilinearArgs ba{plan->d_tasks, v->d_items, static_cast<int64_t>(v->items.size()),
+                          partials, r, s, v->d_item_sums};
+  const bool p_vec = plan->all_n_mult4 && aligned(partials, 16) && aligned(s, 16);
+  CLEAVE_HIP(cleave::launch_bilinear(ba, p_vec, stream));
+
+  cleave::VerdictArgs va{plan->d_tasks, static_cast<int64_t>(plan->tasks.size()),
+                         v->d_task_row_seg, v->d_task_col_seg, v->d_task_first_item,
+                         v->d_item_sums, U, U_abs, V, V_abs, K, tol, lhs, rhs, scale, accept};
+  CLEAVE_HIP(cleave::launch_verdict(va, stream));
   return CLEAVE_OK;
 }

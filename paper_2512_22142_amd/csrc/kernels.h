@@ -48,4 +48,58 @@ struct ReduceArgs {
 hipError_t launch_reduce(const ReduceArgs& args, int out_dtype, bool vec, int grid,
                          hipStream_t stream);
 
+// ---- returned-block check ---------------------------------------------------
+
+// Projection of a stored operand onto a weight vector, once per segment:
+//   out[seg][k]     = sum_{i in seg} x(i, k) * w[seg.start + i]
+//   out_abs[seg][k] = sum_{i in seg} |x(i, k)| * |w[seg.start + i]|
+// for k in [0, K).  reduce_contiguous = false: x(i, k) = src[i * ld + k] (the
+// summed index strides, k is contiguous); true: x(i, k) = src[k * ld + i].
+struct ProjectArgs {
+  const void* src;
+  int64_t ld;               // elements
+  const Segment* segs;
+  int n_segs;
+  const float* w;
+  double* out;
+  double* out_abs;
+  int64_t K;
+};
+hipError_t launch_project(const ProjectArgs& args, int dtype, bool reduce_contiguous, bool vec,
+                          hipStream_t stream);
+
+// item_sums[item] = sum_{rows of the item} r[m0 + i] * sum_j P[i][j] * s[n0 + j].
+struct BilinearArgs {
+  const cleave_task* tasks;
+  const VerifyItem* items;
+  int64_t n_items;
+  const float* partials;
+  const float* r;
+  const float* s;
+  double* item_sums;
+};
+hipError_t launch_bilinear(const BilinearArgs& args, bool vec, hipStream_t stream);
+
+// Per task: lhs = sum of its item sums (ascending), rhs = sum_k U[k] V[k] and
+// scale = sum_k |U|[k] |V|[k] over the task's chunk, accept = |lhs - rhs| <= tol * scale.
+struct VerdictArgs {
+  const cleave_task* tasks;
+  int64_t n_tasks;
+  const uint32_t* task_row_seg;
+  const uint32_t* task_col_seg;
+  const uint32_t* task_first_item;
+  const double* item_sums;
+  const double* U;
+  const double* U_abs;
+  const double* V;
+  const double* V_abs;
+  int64_t K;
+  double tol;
+  double* lhs;      // any of lhs, rhs, scale may be null
+  double* rhs;
+  double* scale;
+  int32_t* accept;
+};
+hipError_t launch_verdict(const VerdictArgs& args, hipStream_t stream);
+
 }  // namespace cleave

@@ -293,4 +293,4 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
-extern "C" int cleave_version(void) { return 100; }
+extern "C" int cleave_version(void) { return 101; }

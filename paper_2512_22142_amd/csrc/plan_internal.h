@@ -52,6 +52,38 @@ struct ReduceItem {
 };
 static_assert(sizeof(ReduceItem) == 16, "ReduceItem is 16 bytes");
 
+// Tables of the returned-block check.  A row segment is a distinct (m0, m_len)
+// of the task list, a column segment a distinct (n0, n_len): the projections
+// of A onto r and of B onto s are computed once per segment and shared by all
+// tasks that use it.
+struct Segment {
+  uint32_t start, len;
+};
+// One unit of work of the bilinear-form kernel: a run of rows of one task's
+// partial block.
+struct VerifyItem {
+  uint32_t task, row0, rows, pad;
+};
+static_assert(sizeof(VerifyItem) == 16, "VerifyItem is 16 bytes");
+
+struct VerifyTables {
+  std::vector<Segment> row_segs, col_segs;
+  std::vector<uint32_t> task_row_seg, task_col_seg;   // per task
+  std::vector<VerifyItem> items;                      // a task's items are adjacent
+  std::vector<uint32_t> task_first_item;              // n_tasks + 1 entries
+  bool segs_mult8 = true;   // every segment start and length a multiple of 8
+  bool segs_mult4 = true;
+  // device copies and scratch (allocated once, on the device the plan lives on)
+  Segment* d_row_segs = nullptr;
+  Segment* d_col_segs = nullptr;
+  uint32_t* d_task_row_seg = nullptr;
+  uint32_t* d_task_col_seg = nullptr;
+  VerifyItem* d_items = nullptr;
+  uint32_t* d_task_first_item = nullptr;
+  double* d_proj = nullptr;       // U, |U| (row segs x K each), V, |V| (col segs x K each)
+  double* d_item_sums = nullptr;  // one per item
+};
+
 // Appends the work items of `task_index` (record t) to out[class].
 void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out);
 
@@ -80,6 +112,9 @@ struct cleave_plan {
   // Scratch for subset launches; grown on demand, reused by later calls.
   cleave::WorkItem* d_subset_items = nullptr;
   int64_t d_subset_capacity = 0;
+
+  // Tables and scratch of the returned-block check; created by its first call.
+  cleave::VerifyTables* verify = nullptr;
 
   const char* last_kernel = "none";
 };

@@ -1,0 +1,173 @@
+"""GPU parity of the returned-block check (cleave_verify through the C ABI)
+against its fp64 oracle.
+
+The partial blocks handed to both sides are synthetic: the oracle's own fp64
+blocks rounded to fp32 (some of them corrupted on purpose -- a mistake planted
+in the data, on the CPU), or seeded random values.  Bars: lhs, rhs, scale within
+1e-12 of the size of the sums they accumulate (both sides sum in fp64, in
+different orders); accept flags identical (the cases sit far from the
+threshold); everything bit-exact for integer-valued inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_22142_amd as cleave
+from oracle import gemm as og
+from oracle import planner
+from oracle import verify as ov
+from workloads import draw_explicit_tiling
+from workloads.tensors import make_matrix, make_probe_vectors
+
+from gpu_util import stored
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
+
+
+def gpu_verify(plan, A, B, transA, transB, partials, r, s, tol):
+    n = plan.num_tasks
+    out = {k: torch.full((n,), float("nan"), dtype=torch.float64, device="cuda") for k in ("lhs", "rhs", "scale")}
+    accept = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    cleave.verify(plan, A.cuda(), B.cuda(), torch.from_numpy(partials).cuda(), r.cuda(), s.cuda(), tol,
+                  accept, out["lhs"], out["rhs"], out["scale"], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    return out["lhs"].cpu().numpy(), out["rhs"].cpu().numpy(), out["scale"].cpu().numpy(), accept.cpu().numpy()
+
+
+def oracle_partials(tasks, opA, opB, elems, corrupt=()):
+    """fp32 roundings of the oracle's blocks; tasks listed in `corrupt` get one entry changed."""
+    parts = og.execute_tasks(tasks, opA, opB, elems).astype(np.float32)
+    for i in corrupt:
+        t = tasks[i]
+        cnt = int(t["m_len"]) * int(t["n_len"])
+        pos = int(t["partial_off"]) + (7 * i + 3) % cnt
+        parts[pos] += np.float32(1000.0)   # large against tol * scale / |r_i s_j| for these shapes
+    return parts
+
+
+def lhs_size(tasks, parts, r, s):
+    """sum |r_i| |P_ij| |s_j| per task: the size of what lhs accumulates."""
+    out = np.zeros(len(tasks))
+    for i, t in enumerate(tasks):
+        m0, ml, n0, nl = (int(t[f]) for f in ("m0", "m_len", "n0", "n_len"))
+        off = int(t["partial_off"])
+        P = np.abs(parts[off:off + ml * nl].astype(np.float64)).reshape(ml, nl)
+        out[i] = np.abs(r[m0:m0 + ml]) @ P @ np.abs(s[n0:n0 + nl])
+    return out
+
+
+def compare(tasks, got, ref, sizes):
+    lhs, rhs, scale, accept = got
+    lhs_r, rhs_r, scale_r, accept_r = ref
+    assert np.all(np.abs(lhs - lhs_r) <= 1e-12 * sizes + 1e-300)
+    assert np.all(np.abs(rhs - rhs_r) <= 1e-12 * scale_r + 1e-300)
+    assert np.all(np.abs(scale - scale_r) <= 1e-12 * scale_r + 1e-300)
+    assert np.array_equal(accept, accept_r)
+
+
+# several tiles and a ragged tail; the first shapes keep the 16-byte paths, the others do not
+SHAPES = [
+    (256, 384, 192, 128, 128, 3), (640, 392, 512, 256, 256, 2), (300, 200, 72, 128, 128, 3),
+    (37, 29, 50, 16, 8, 2), (130, 150, 10, 64, 64, 3), (96, 260, 64, 96, 260, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("M,N,K,tm,tn,S", SHAPES)
+def test_verify_matches_oracle(M, N, K, tm, tn, S, transA, transB, dtype):
+    A_log = make_matrix(31 + M, M, K, dtype)
+    B_log = make_matrix(32 + N, K, N, dtype, std=0.02)
+    A, B = stored(A_log, transA), stored(B_log, transB)
+    r, s = make_probe_vectors(33 + K, M, N)
+    plan = cleave.plan_uniform(M, N, K, tm, tn, S)
+    tasks, elems = planner.plan_uniform(M, N, K, tm, tn, S)
+    opA, opB = og.logical_operands(A, transA, B, transB)
+    bad = list(range(1, len(tasks), 3))
+    parts = oracle_partials(tasks, opA, opB, elems, corrupt=bad)
+    tol = 1e-6
+    ref = ov.verify_tasks(tasks, opA, opB, parts, r.numpy(), s.numpy(), tol)
+    got = gpu_verify(plan, A, B, transA, transB, parts, r, s, tol)
+    compare(tasks, got, ref, lhs_size(tasks, parts, r.numpy(), s.numpy()))
+    # the planted corruptions, and only they, are rejected
+    assert set(np.flatnonzero(got[3] == 0)) == set(bad)
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_verify_is_exact_on_integer_inputs(transA, transB, dtype):
+    M, N, K, tm, tn, S = 384, 264, 256, 128, 88, 4
+    A_log = make_matrix(41, M, K, dtype, integer_valued=True)
+    B_log = make_matrix(42, K, N, dtype, integer_valued=True)
+    A, B = stored(A_log, transA), stored(B_log, transB)
+    r, s = make_probe_vectors(43, M, N, kind="sign")
+    plan = cleave.plan_uniform(M, N, K, tm, tn, S)
+    tasks, elems = planner.plan_uniform(M, N, K, tm, tn, S)
+    opA, opB = og.logical_operands(A, transA, B, transB)
+    parts = og.execute_tasks(tasks, opA, opB, elems).astype(np.float32)   # exact integers
+    bad = [0, 5, len(tasks) - 1]
+    for i in bad:
+        parts[int(tasks[i]["partial_off"]) + 11 * i] += 1.0
+    ref = ov.verify_tasks(tasks, opA, opB, parts, r.numpy(), s.numpy(), 0.0)
+    lhs, rhs, scale, accept = gpu_verify(plan, A, B, transA, transB, parts, r, s, 0.0)
+    assert np.array_equal(lhs, ref[0]) and np.array_equal(rhs, ref[1]) and np.array_equal(scale, ref[2])
+    assert np.array_equal(accept, ref[3])
+    assert np.array_equal(np.abs(lhs - rhs) == 1.0, accept == 0)
+    assert set(np.flatnonzero(accept == 0)) == set(bad)
+
+
+def test_verify_heterogeneous_tiling():
+    M, N, K = 1536, 1280, 512
+    band_h, col_w, ks = draw_explicit_tiling(M, N, K, seed=77)
+    plan = cleave.plan_explicit(M, N, K, band_h, col_w, ks)
+    tasks, elems = planner.plan_explicit(M, N, K, band_h, col_w, ks)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    A = make_matrix(51, M, K)
+    B = make_matrix(52, K, N, std=0.02)
+    r, s = make_probe_vectors(53, M, N)
+    opA, opB = og.logical_operands(A, 0, B, 0)
+    bad = list(range(0, len(tasks), 7))
+    parts = oracle_partials(tasks, opA, opB, elems, corrupt=bad)
+    ref = ov.verify_tasks(tasks, opA, opB, parts, r.numpy(), s.numpy(), 1e-6)
+    got = gpu_verify(plan, A, B, 0, 0, parts, r, s, 1e-6)
+    compare(tasks, got, ref, lhs_size(tasks, parts, r.numpy(), s.numpy()))
+    assert set(np.flatnonzero(got[3] == 0)) == set(bad)
+
+
+def test_verify_after_execute_accepts_honest_blocks_and_flags_tampered_ones():
+    """End to end on the device: blocks written by cleave_execute pass, blocks
+    overwritten afterwards do not (a property; no oracle values involved)."""
+    M, N, K, transA, transB = 1024, 1536, 2048, 0, 0
+    A = make_matrix(61, M, K).cuda()
+    B = make_matrix(62, K, N, std=0.02).cuda()
+    r, s = (v.cuda() for v in make_probe_vectors(63, M, N))
+    plan = cleave.plan_uniform(M, N, K, 512, 512, 4)
+    parts = torch.empty(plan.partial_elems, dtype=torch.float32, device="cuda")
+    cleave.execute(plan, A, B, parts, transA, transB)
+    accept = torch.empty(plan.num_tasks, dtype=torch.int32, device="cuda")
+    cleave.verify(plan, A, B, parts, r, s, 1e-6, accept)
+    assert bool((accept == 1).all())
+    tasks = plan.tasks
+    bad = [2, 9, 17]
+    for i in bad:
+        parts[int(tasks[i]["partial_off"]) + 1000 + i] += 1000.0
+    cleave.verify(plan, A, B, parts, r, s, 1e-6, accept)
+    torch.cuda.synchronize()
+    assert set(np.flatnonzero(accept.cpu().numpy() == 0)) == set(bad)
+
+
+def test_verify_rejects_bad_arguments():
+    plan = cleave.plan_uniform(64, 64, 64, 32, 32, 1)
+    A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    parts = torch.zeros(plan.partial_elems, device="cuda")
+    r = torch.zeros(64, device="cuda")
+    accept = torch.zeros(plan.num_tasks, dtype=torch.int32, device="cuda")
+    with pytest.raises(cleave.CleaveError) as e:
+        cleave.verify(plan, A, A, parts, r, r, -1.0, accept)
+    assert e.value.status == -1
+    with pytest.raises(cleave.CleaveError):
+        cleave.verify(plan, A, A, parts, r, r, float("nan"), accept)
+    with pytest.raises(ValueError):
+        cleave.verify(plan, A, A, parts, r[:10], r, 0.0, accept)
