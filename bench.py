@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
@@ -221,6 +222,41 @@ def main():
         "paper_context": "paper reports cost-model times only (e.g. LLaMA-13B fwd GEMMs 0.063 s/step "
                          "at A100 peak rate, Table 2); no measured kernel numbers",
     }
+
+    # ---- returned-block check (outside the timed step; reported on its own) -
+    if not args.no_verify:
+        from workloads import make_probe_vectors
+        probes, outs = [], []
+        for i, (g, plan, _, _) in enumerate(gemms):
+            r, s = make_probe_vectors(cfg.seed * 100 + i, g.M, g.N)
+            probes.append((r.cuda(), s.cuda()))
+            outs.append(torch.empty(plan.num_tasks, dtype=torch.int32, device="cuda"))
+        ver_ms = [0.0] * len(gemms)
+        reps = max(3, args.steps // 4)
+        for rep in range(reps + 1):                      # first pass: warm-up (allocates the plan's scratch)
+            for i, (g, plan, dA, dB) in enumerate(gemms):
+                cleave.execute(plan, dA, dB, slots[i], g.transA, g.transB)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                cleave.verify(plan, dA, dB, slots[i], probes[i][0], probes[i][1], 1e-6, outs[i],
+                              transA=g.transA, transB=g.transB)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                if rep > 0:
+                    ver_ms[i] += e0.elapsed_time(e1) / reps
+        accepted = sum(int(o.sum().item()) for o in outs)
+        ver_bytes = [plan.partial_elems * 4 + (g.M * g.K + g.K * g.N) * in_bytes + (g.M + g.N) * 4
+                     for g, plan, _, _ in gemms]
+        ver_gbps = sum(ver_bytes) / (sum(ver_ms) * 1e-3) / 1e9
+        result["verify_roofline"] = {
+            "kernel": "verify (projections + bilinear form + verdict)", "bound": "hbm",
+            "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+            "frac": round(ver_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+            "ms_per_layer": round(sum(ver_ms), 4),
+            "bytes_per_call_avg": sum(ver_bytes) / len(gemms),
+            "tasks_accepted": accepted, "tasks": sum(p.num_tasks for _, p, _, _ in gemms),
+            "note": "blocks written by execute, tol 1e-6; not part of the timed step",
+        }
 
     # ---- CPU baseline: the oracle as it stands, bounded sample -------------
     if not args.no_cpu_baseline:

@@ -290,7 +290,7 @@ int ensure_verify_tables(cleave_plan* p) {
     if (!v) return CLEAVE_ENOMEM;
     try {
       std::map<std::pair<uint32_t, uint32_t>, uint32_t> rows, cols;
-      constexpr uint32_t kElemsPerItem = 65536;
+      constexpr uint32_t kElemsPerItem = 16384;
       v->task_first_item.push_back(0);
       for (const cleave_task& t : p->tasks) {
         auto ri = rows.emplace(std::make_pair(t.m0, t.m_len), static_cast<uint32_t>(rows.size()));
@@ -375,24 +375,22 @@ extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int 
   double* V_abs = V + v->col_segs.size() * static_cast<size_t>(K);
 
   // op(A)[i][k]: stored M x K (transA = 0) -> the summed row index strides;
-  // stored K x M (transA = 1) -> it is contiguous.
-  cleave::ProjectArgs pa{A, lda, v->d_row_segs, static_cast<int>(v->row_segs.size()), r, U, U_abs, K};
+  // stored K x M (transA = 1) -> it is contiguous.  op(B)[k][j]: stored K x N
+  // (transB = 0) -> the summed column index is contiguous; stored N x K -> it
+  // strides.
   const bool a_contig = transA != 0;
+  const bool b_contig = transB == 0;
   const bool a_vec = aligned(A, 16) && lda % e == 0 &&
                      (a_contig ? (segs_ok && aligned(r, 16)) : K % e == 0);
-  CLEAVE_HIP(cleave::launch_project(pa, dtype, a_contig, a_vec, stream));
-  // op(B)[k][j]: stored K x N (transB = 0) -> the summed column index is
-  // contiguous; stored N x K (transB = 1) -> it strides.
-  cleave::ProjectArgs pb{B, ldb, v->d_col_segs, static_cast<int>(v->col_segs.size()), s, V, V_abs, K};
-  const bool b_contig = transB == 0;
   const bool b_vec = aligned(B, 16) && ldb % e == 0 &&
                      (b_contig ? (segs_ok && aligned(s, 16)) : K % e == 0);
-  CLEAVE_HIP(cleave::launch_project(pb, dtype, b_contig, b_vec, stream));
-
-  cleave::BilinearArgs ba{plan->d_tasks, v->d_items, static_cast<int64_t>(v->items.size()),
-                          partials, r, s, v->d_item_sums};
   const bool p_vec = plan->all_n_mult4 && aligned(partials, 16) && aligned(s, 16);
-  CLEAVE_HIP(cleave::launch_bilinear(ba, p_vec, stream));
+  cleave::VerifyPassArgs pass{};
+  pass.A = cleave::ProjectArgs{A, lda, v->d_row_segs, static_cast<int>(v->row_segs.size()), r, U, U_abs, K};
+  pass.B = cleave::ProjectArgs{B, ldb, v->d_col_segs, static_cast<int>(v->col_segs.size()), s, V, V_abs, K};
+  pass.bil = cleave::BilinearArgs{plan->d_tasks, v->d_items, static_cast<int64_t>(v->items.size()),
+                                  partials, r, s, v->d_item_sums};
+  CLEAVE_HIP(cleave::launch_verify_pass(pass, dtype, a_contig, b_contig, a_vec && b_vec && p_vec, stream));
 
   cleave::VerdictArgs va{plan->d_tasks, static_cast<int64_t>(plan->tasks.size()),
                          v->d_task_row_seg, v->d_task_col_seg, v->d_task_first_item,

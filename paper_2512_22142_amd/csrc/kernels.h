@@ -65,8 +65,6 @@ struct ProjectArgs {
   double* out_abs;
   int64_t K;
 };
-hipError_t launch_project(const ProjectArgs& args, int dtype, bool reduce_contiguous, bool vec,
-                          hipStream_t stream);
 
 // item_sums[item] = sum_{rows of the item} r[m0 + i] * sum_j P[i][j] * s[n0 + j].
 struct BilinearArgs {
@@ -78,7 +76,17 @@ struct BilinearArgs {
   const float* s;
   double* item_sums;
 };
-hipError_t launch_bilinear(const BilinearArgs& args, bool vec, hipStream_t stream);
+
+// The two projections and the bilinear items in one launch.  a_contig /
+// b_contig: the summed index of that operand is the contiguous one.  `vec`
+// selects 16-byte loads for all three jobs (caller has checked alignment and
+// divisibility for all of them).
+struct VerifyPassArgs {
+  ProjectArgs A, B;
+  BilinearArgs bil;
+};
+hipError_t launch_verify_pass(const VerifyPassArgs& args, int dtype, bool a_contig, bool b_contig,
+                              bool vec, hipStream_t stream);
 
 // Per task: lhs = sum of its item sums (ascending), rhs = sum_k U[k] V[k] and
 // scale = sum_k |U|[k] |V|[k] over the task's chunk, accept = |lhs - rhs| <= tol * scale.

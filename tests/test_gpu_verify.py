@@ -171,3 +171,63 @@ def test_verify_rejects_bad_arguments():
         cleave.verify(plan, A, A, parts, r, r, float("nan"), accept)
     with pytest.raises(ValueError):
         cleave.verify(plan, A, A, parts, r[:10], r, 0.0, accept)
+
+
+def _full_size_check(g, plan, tasks, cfg, cache, seed, n_samples=6):
+    """cleave_verify over a whole GEMM of a benchmark configuration; seeded random
+    fp32 values stand in for the partial blocks; sampled tasks (always the last,
+    ragged one) against the oracle, one by one."""
+    from workloads import make_gemm_operands
+    A, B = make_gemm_operands(cfg, g, cache=cache)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    parts = torch.randn(plan.partial_elems, generator=gen, dtype=torch.float32)
+    r, s = make_probe_vectors(seed + 1, g.M, g.N)
+    n = plan.num_tasks
+    lhs, rhs, scale = (torch.empty(n, dtype=torch.float64, device="cuda") for _ in range(3))
+    accept = torch.empty(n, dtype=torch.int32, device="cuda")
+    cleave.verify(plan, A.cuda(), B.cuda(), parts.cuda(), r.cuda(), s.cuda(), 1e-6, accept, lhs, rhs, scale,
+                  transA=g.transA, transB=g.transB)
+    torch.cuda.synchronize()
+    lhs, rhs, scale, accept = (x.cpu().numpy() for x in (lhs, rhs, scale, accept))
+    opA, opB = og.logical_operands(A, g.transA, B, g.transB)
+    rng = np.random.default_rng(seed)
+    picks = sorted({n - 1, 0} | {int(i) for i in rng.integers(0, n, n_samples)})
+    pn, rn, sn = parts.numpy(), r.numpy(), s.numpy()
+    for i in picks:
+        t = tasks[i]
+        off, cnt = int(t["partial_off"]), int(t["m_len"]) * int(t["n_len"])
+        l, h, sc, ok = ov.verify_task(opA, opB, pn[off:off + cnt], t, rn, sn, 1e-6)
+        size = lhs_size(tasks[i:i + 1], pn, rn, sn)[0]
+        assert abs(lhs[i] - l) <= 1e-12 * size, (g.name, i)
+        assert abs(rhs[i] - h) <= 1e-12 * sc and abs(scale[i] - sc) <= 1e-12 * sc, (g.name, i)
+        assert accept[i] == int(ok), (g.name, i)
+    assert accept.sum() <= n // 20      # random blocks are not the products; a few may pass by chance
+
+
+def test_verify_c3_full_size_sampled():
+    from workloads import layer_config
+    cfg = layer_config("c3")
+    cache = {}
+    for gid, g in enumerate(cfg.gemms):
+        if g.name not in ("q.fwd", "gate.fwd", "down.dx", "up.dw"):
+            continue
+        plan = cleave.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
+        tasks, _ = planner.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
+        _full_size_check(g, plan, tasks, cfg, cache, seed=7000 + gid)
+        print("c3 verify", g.name, plan.num_tasks, "tasks", flush=True)
+
+
+def test_verify_c4_heterogeneous_full_size_sampled():
+    from workloads import layer_config
+    from workloads.configs import C4_TILING_SEED
+    cfg = layer_config("c4")
+    cache = {}
+    for gid, g in enumerate(cfg.gemms):
+        if g.name not in ("gate.fwd", "down.dw"):
+            continue
+        band_h, col_w, ks = draw_explicit_tiling(g.M, g.N, g.K, C4_TILING_SEED + gid)
+        plan = cleave.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
+        tasks, _ = planner.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
+        _full_size_check(g, plan, tasks, cfg, cache, seed=7100 + gid)
+        print("c4 verify", g.name, plan.num_tasks, "tasks", flush=True)
