@@ -146,6 +146,23 @@ def reduce_partials(tasks, partials, M, N):
     return C
 
 
+def batch_view(stored, g, n_inner, outer_stride, inner_stride, rows, cols):
+    """Zero-copy view of GEMM g's stored operand inside a larger 2-D array:
+    g = o * n_inner + i starts at flat element o * outer_stride + i * inner_stride
+    of `stored` (row-major, leading dimension = its row length) and spans
+    rows x cols with the same leading dimension -- the boundary's batch
+    convention.  Returns an ndarray view (no arithmetic)."""
+    ld = stored.shape[1]
+    o, i = divmod(g, n_inner)
+    start = o * outer_stride + i * inner_stride
+    flat = stored.reshape(-1)
+    span = (rows - 1) * ld + cols
+    if start < 0 or start + span > flat.size:
+        raise ValueError("batch view out of range")
+    return np.lib.stride_tricks.as_strided(flat[start:], shape=(rows, cols),
+                                           strides=(ld * flat.itemsize, flat.itemsize), writeable=False)
+
+
 def rel_frobenius(C, C_ref):
     """||C - C_ref||_F / ||C_ref||_F in fp64."""
     c = np.asarray(C, dtype=np.float64)

@@ -130,6 +130,25 @@ def plan_explicit(M, N, K, band_h, col_w, ksplit_per_tile, gemm_id=0):
     return _emit(tiles, K, gemm_id)
 
 
+def plan_batched(M, N, K, tile_m, tile_n, ksplit, n_batch):
+    """A batch of n_batch independent GEMMs of one shape in one task list (the
+    per-head score GEMMs of Sec. 3.1, Table "GEMM shapes": Q x K^T is
+    1024 x 128 x 1024, one per sequence and head).  GEMM g contributes the
+    uniform plan of a single GEMM with gemm_id = g; its tile ids start at 0
+    again; partial offsets continue through the whole list.
+    Returns (tasks, partial_elems)."""
+    if n_batch < 1:
+        raise PlanError("empty batch")
+    one, elems = plan_uniform(M, N, K, tile_m, tile_n, ksplit, 0)
+    parts = []
+    for g in range(n_batch):
+        t = one.copy()
+        t["gemm_id"] = g
+        t["partial_off"] += g * elems
+        parts.append(t)
+    return np.concatenate(parts), elems * n_batch
+
+
 # ---------------------------------------------------------------------------
 # Invariant checkers (the constraints the paper fixes for any valid plan).
 # ---------------------------------------------------------------------------

@@ -169,3 +169,21 @@ def test_projection_check_accepts_product_and_detects_one_bad_entry():
     bad[17, 60] += 1.0
     assert og.projection_check(a, b, bad, seed=1) > 1e-6
     assert og.projection_check(a, b, c.T.copy().T * (1 + 1e-3), seed=2) > 1e-5
+
+
+def test_batch_view_is_the_head_slice_of_a_token_major_activation():
+    # Q stored [T, H*d], token-major: sequence o, head i is rows o*s..(o+1)*s, columns i*d..(i+1)*d
+    s_len, H, d, n_seq = 6, 3, 4, 2
+    Q = np.arange(n_seq * s_len * H * d, dtype=np.float64).reshape(n_seq * s_len, H * d)
+    ld = H * d
+    for g in range(n_seq * H):
+        o, i = divmod(g, H)
+        v = og.batch_view(Q, g, H, s_len * ld, d, s_len, d)
+        assert np.array_equal(v, Q[o * s_len:(o + 1) * s_len, i * d:(i + 1) * d])
+    # contiguous per-GEMM blocks (scores [n_seq*H, s, s]): stride s*s, ld = s
+    P = np.arange(n_seq * H * s_len * s_len, dtype=np.float64).reshape(n_seq * H * s_len, s_len)
+    for g in range(n_seq * H):
+        v = og.batch_view(P, g, H, H * s_len * s_len, s_len * s_len, s_len, s_len)
+        assert np.array_equal(v, P[g * s_len:(g + 1) * s_len, :])
+    with pytest.raises(ValueError):
+        og.batch_view(Q, n_seq * H, H, s_len * ld, d, s_len, d)

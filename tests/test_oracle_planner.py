@@ -152,3 +152,27 @@ def test_invariant_checker_catches_planted_mistakes():
             planner.check_plan_invariants(bad, 64, 64, 32)
     with pytest.raises(AssertionError):      # a task listed twice = redundant work
         planner.check_plan_invariants(np.concatenate([tasks, tasks[-1:]]), 64, 64, 32)
+
+
+def test_batched_plan_is_the_single_plan_repeated_with_running_offsets():
+    M, N, K, tm, tn, S, G = 20, 12, 16, 8, 8, 2, 5
+    tasks, elems = planner.plan_batched(M, N, K, tm, tn, S, G)
+    one, one_elems = planner.plan_uniform(M, N, K, tm, tn, S)
+    assert elems == G * M * N * S == G * one_elems and len(tasks) == G * len(one)
+    for g in range(G):
+        part = tasks[g * len(one):(g + 1) * len(one)].copy()
+        assert np.all(part["gemm_id"] == g)
+        # each member alone is a valid plan of the single GEMM
+        local = part.copy()
+        local["partial_off"] -= g * one_elems
+        local["gemm_id"] = 0
+        assert local.tobytes() == one.tobytes()
+        planner.check_plan_invariants(local, M, N, K)
+    # blocks are disjoint and cover [0, elems) exactly
+    sizes = tasks["m_len"].astype(np.int64) * tasks["n_len"]
+    assert np.array_equal(tasks["partial_off"], np.concatenate([[0], np.cumsum(sizes)[:-1]]))
+    # attention-score shape of the paper's table: 1024 x 128 x 1024 per head, K too short to split
+    t, e = planner.plan_batched(1024, 1024, 128, 512, 512, 1, 128)
+    assert len(t) == 128 * 4 and e == 128 * 1024 * 1024
+    with pytest.raises(planner.PlanError):
+        planner.plan_batched(8, 8, 8, 4, 4, 1, 0)
