@@ -106,6 +106,17 @@ int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_bands, const
                          const int32_t* n_cols, const int64_t* col_w,
                          const int32_t* ksplit_per_tile, uint32_t gemm_id, cleave_plan** out);
 
+/* A batch of n_batch independent GEMMs of one shape M x N x K in one task
+ * list (paper Sec. 3.1, table of GEMM shapes: the attention-score products
+ * Q K^T are 1024 x 128 x 1024, one per sequence and head, and share a DAG
+ * level).  Member g contributes the uniform plan of a single GEMM with
+ * gemm_id = g: tile ids restart at 0, partial offsets run on through the whole
+ * list.  The plan is used with cleave_execute_batched / cleave_reduce_batched
+ * (the plain calls return CLEAVE_EINVAL on it, and the batched calls on a
+ * plain plan).  CLEAVE_EINVAL as for cleave_plan_uniform, or n_batch < 1. */
+int cleave_plan_batched(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
+                        int32_t ksplit, int64_t n_batch, cleave_plan** out);
+
 int64_t cleave_plan_num_tasks(const cleave_plan* plan);
 int64_t cleave_plan_num_tiles(const cleave_plan* plan);
 /* Host array of num_tasks records; borrowed, valid until cleave_plan_destroy. */
@@ -136,6 +147,19 @@ int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
                    const void* B, int64_t ldb, int transB,
                    int dtype, float* partials, void* hip_stream);
 
+/* Batched form of cleave_execute for a plan made by cleave_plan_batched.
+ * Member g = o * n_inner + i (0 <= i < n_inner, n_inner divides n_batch) reads
+ * its operands as zero-copy views: its stored A starts a_outer * o + a_inner * i
+ * elements after `A` and has leading dimension lda; B likewise.  Example, Q and
+ * K stored token-major [tokens, heads * d]: n_inner = heads, a_outer = seq *
+ * lda, a_inner = d, transB = 1 with the same strides for K.  Strides are
+ * non-negative element counts; the caller guarantees that every view lies
+ * inside its allocation.  Everything else as for cleave_execute. */
+int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                           const void* A, int64_t lda, int transA, int64_t a_outer, int64_t a_inner,
+                           const void* B, int64_t ldb, int transB, int64_t b_outer, int64_t b_inner,
+                           int64_t n_inner, int dtype, float* partials, void* hip_stream);
+
 /* ---- reduce --------------------------------------------------------------
  * C[m0+i, n0+j] = ((P_0[i,j] + P_1[i,j]) + ...) + P_{S-1}[i,j] for every tile.
  * partials: device fp32, as written by cleave_execute.  C: device, M x N
@@ -144,6 +168,12 @@ int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
  * output is a bitwise copy of the single partial. */
 int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
                   int out_dtype, void* hip_stream);
+
+/* Batched form of cleave_reduce: member g = o * n_inner + i writes its M x N
+ * result c_outer * o + c_inner * i elements after `C`, leading dimension ldc. */
+int cleave_reduce_batched(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
+                          int64_t c_outer, int64_t c_inner, int64_t n_inner,
+                          int out_dtype, void* hip_stream);
 
 /* ---- verify --------------------------------------------------------------
  * Check of returned partial blocks by random projection (paper Sec. 6,
@@ -166,7 +196,7 @@ int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc
  * the operands per distinct row / column range of the tiling, per-item sums);
  * two verify calls on one plan must not overlap in time.
  * CLEAVE_EINVAL: NULL or misaligned pointer, bad enum, short leading
- * dimension, negative or NaN tol. */
+ * dimension, negative or NaN tol, or a batched plan. */
 int cleave_verify(cleave_plan* plan,
                   const void* A, int64_t lda, int transA,
                   const void* B, int64_t ldb, int transB, int dtype,

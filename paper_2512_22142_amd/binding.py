@@ -34,7 +34,8 @@ EXPORTS = (
     "cleave_plan_num_tiles", "cleave_plan_tasks", "cleave_plan_partial_elems",
     "cleave_plan_dims", "cleave_plan_upload", "cleave_plan_destroy", "cleave_execute",
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
-    "cleave_plan_last_kernel", "cleave_verify",
+    "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
+    "cleave_reduce_batched",
 )
 
 
@@ -78,6 +79,13 @@ def _load():
                                    ctypes.c_int, p, p]
     lib.cleave_execute.restype = ctypes.c_int
     lib.cleave_reduce.argtypes = [p, p, p, i64, ctypes.c_int, p]
+    lib.cleave_plan_batched.argtypes = [i64, i64, i64, i64, i64, i32, i64, ctypes.POINTER(p)]
+    lib.cleave_plan_batched.restype = ctypes.c_int
+    lib.cleave_execute_batched.argtypes = [p, p, i64, p, i64, ctypes.c_int, i64, i64,
+                                           p, i64, ctypes.c_int, i64, i64, i64, ctypes.c_int, p, p]
+    lib.cleave_execute_batched.restype = ctypes.c_int
+    lib.cleave_reduce_batched.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p]
+    lib.cleave_reduce_batched.restype = ctypes.c_int
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
@@ -219,6 +227,51 @@ def reduce(plan, partials, C, stream=None):
         raise ValueError("C must be M x N")
     _check(_lib.cleave_reduce(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
                               _dtype_code(C), _stream_ptr(stream)), "cleave_reduce")
+
+
+def plan_batched(M, N, K, tile_m, tile_n, ksplit, n_batch):
+    h = ctypes.c_void_p()
+    _check(_lib.cleave_plan_batched(M, N, K, tile_m, tile_n, ksplit, n_batch, ctypes.byref(h)),
+           "cleave_plan_batched")
+    return Plan(h.value)
+
+
+def _device_2d(t, what):
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise ValueError("%s must be a 2-D device tensor with unit column stride" % what)
+    return ctypes.c_void_p(t.data_ptr()), int(t.stride(0))
+
+
+def execute_batched(plan, A, a_strides, B, b_strides, n_inner, partials, transA=0, transB=0,
+                    task_ids=None, stream=None):
+    """cleave_execute_batched: A, B are the 2-D device tensors that hold every
+    member's operand (leading dimension = their row stride); a_strides /
+    b_strides = (outer, inner) element strides between members."""
+    import torch
+    a_ptr, lda = _device_2d(A, "A")
+    b_ptr, ldb = _device_2d(B, "B")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    if partials.dtype != torch.float32 or not partials.is_cuda or not partials.is_contiguous() \
+            or partials.numel() < plan.partial_elems:
+        raise ValueError("partials must be a contiguous fp32 device tensor of partial_elems elements")
+    ids_ptr, n_ids = None, 0
+    if task_ids is not None:
+        ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+        ids_ptr, n_ids = ctypes.c_void_p(ids.ctypes.data), len(ids)
+    _check(_lib.cleave_execute_batched(
+        plan._h, ids_ptr, n_ids, a_ptr, lda, int(transA), int(a_strides[0]), int(a_strides[1]),
+        b_ptr, ldb, int(transB), int(b_strides[0]), int(b_strides[1]), int(n_inner),
+        _dtype_code(A), ctypes.c_void_p(partials.data_ptr()), _stream_ptr(stream)),
+        "cleave_execute_batched")
+
+
+def reduce_batched(plan, partials, C, c_strides, n_inner, stream=None):
+    """cleave_reduce_batched: C the 2-D device tensor that holds every member's result."""
+    c_ptr, ldc = _device_2d(C, "C")
+    _check(_lib.cleave_reduce_batched(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
+                                      int(c_strides[0]), int(c_strides[1]), int(n_inner),
+                                      _dtype_code(C), _stream_ptr(stream)), "cleave_reduce_batched")
 
 
 def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=None,

@@ -135,9 +135,17 @@ extern "C" void cleave_plan_destroy(cleave_plan* plan) {
   delete plan;
 }
 
-extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
-                              const void* A, int64_t lda, int transA, const void* B, int64_t ldb,
-                              int transB, int dtype, float* partials, void* hip_stream) {
+namespace {
+
+// Strides of a batched call, in elements; n_inner = 0 for a plain plan.
+struct BatchStrides {
+  int64_t n_inner = 0;
+  int64_t a_outer = 0, a_inner = 0, b_outer = 0, b_inner = 0;
+};
+
+int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, const void* A,
+                 int64_t lda, int transA, const void* B, int64_t ldb, int transB, int dtype,
+                 float* partials, const BatchStrides& bs, void* hip_stream) {
   if (!plan || !A || !B || !partials) return CLEAVE_EINVAL;
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
@@ -173,7 +181,9 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
                            : (plan->all_k_mult4 && plan->all_mn_mult4)) &&
                    lda % e == 0 && ldb % e == 0 && aligned(A, 16) && aligned(B, 16) &&
                    // in-tile byte offsets are kept in 32 bits
-                   lda * eb < (int64_t{1} << 22) && ldb * eb < (int64_t{1} << 22);
+                   lda * eb < (int64_t{1} << 22) && ldb * eb < (int64_t{1} << 22) &&
+                   bs.a_outer % e == 0 && bs.a_inner % e == 0 && bs.b_outer % e == 0 &&
+                   bs.b_inner % e == 0;
 
   const cleave::WorkItem* d_lists[cleave::kNumTileClasses] = {plan->d_items[0], plan->d_items[1]};
   int64_t counts[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items[0].size()),
@@ -221,6 +231,11 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
     args.transA = transA;
     args.transB = transB;
     args.partials = partials;
+    args.batch_inner = static_cast<uint32_t>(bs.n_inner);
+    args.a_outer = bs.a_outer;
+    args.a_inner = bs.a_inner;
+    args.b_outer = bs.b_outer;
+    args.b_inner = bs.b_inner;
     const bool direct = vec && dtype == CLEAVE_BF16 &&
                         (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
     if (direct) {
@@ -250,8 +265,39 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
   return CLEAVE_OK;
 }
 
-extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
-                             int out_dtype, void* hip_stream) {
+}  // namespace
+
+extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                              const void* A, int64_t lda, int transA, const void* B, int64_t ldb,
+                              int transB, int dtype, float* partials, void* hip_stream) {
+  if (plan && plan->batch > 0) return CLEAVE_EINVAL;   // batched plans use the batched call
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials,
+                      BatchStrides{}, hip_stream);
+}
+
+extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                                      const void* A, int64_t lda, int transA, int64_t a_outer,
+                                      int64_t a_inner, const void* B, int64_t ldb, int transB,
+                                      int64_t b_outer, int64_t b_inner, int64_t n_inner, int dtype,
+                                      float* partials, void* hip_stream) {
+  if (!plan || plan->batch < 1) return CLEAVE_EINVAL;
+  if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
+    return CLEAVE_EINVAL;
+  if (a_outer < 0 || a_inner < 0 || b_outer < 0 || b_inner < 0) return CLEAVE_EINVAL;
+  BatchStrides bs;
+  bs.n_inner = n_inner;
+  bs.a_outer = a_outer;
+  bs.a_inner = a_inner;
+  bs.b_outer = b_outer;
+  bs.b_inner = b_inner;
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials, bs,
+                      hip_stream);
+}
+
+namespace {
+
+int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, int out_dtype,
+                int64_t n_inner, int64_t c_outer, int64_t c_inner, void* hip_stream) {
   if (!plan || !partials || !C) return CLEAVE_EINVAL;
   if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if (ldc < plan->N) return CLEAVE_EINVAL;
@@ -265,7 +311,8 @@ extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, 
   rc = compute_units(&cus);
   if (rc != CLEAVE_OK) return rc;
 
-  const bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob);
+  const bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
+                   c_outer % 4 == 0 && c_inner % 4 == 0;
   cleave::ReduceArgs args{};
   args.tasks = plan->d_tasks;
   args.items = plan->d_reduce_items;
@@ -273,9 +320,30 @@ extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, 
   args.partials = partials;
   args.C = C;
   args.ldc = ldc;
+  args.batch_inner = static_cast<uint32_t>(n_inner);
+  args.c_outer = c_outer;
+  args.c_inner = c_inner;
   const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20)); (void)cus;
   CLEAVE_HIP(cleave::launch_reduce(args, out_dtype, vec, grid, stream));
   return CLEAVE_OK;
+}
+
+}  // namespace
+
+extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
+                             int out_dtype, void* hip_stream) {
+  if (plan && plan->batch > 0) return CLEAVE_EINVAL;
+  return reduce_impl(plan, partials, C, ldc, out_dtype, 0, 0, 0, hip_stream);
+}
+
+extern "C" int cleave_reduce_batched(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
+                                     int64_t c_outer, int64_t c_inner, int64_t n_inner,
+                                     int out_dtype, void* hip_stream) {
+  if (!plan || plan->batch < 1) return CLEAVE_EINVAL;
+  if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
+    return CLEAVE_EINVAL;
+  if (c_outer < 0 || c_inner < 0) return CLEAVE_EINVAL;
+  return reduce_impl(plan, partials, C, ldc, out_dtype, n_inner, c_outer, c_inner, hip_stream);
 }
 
 namespace {
@@ -348,6 +416,7 @@ extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int 
                              double* lhs, double* rhs, double* scale, int32_t* accept,
                              void* hip_stream) {
   if (!plan || !A || !B || !partials || !r || !s || !accept) return CLEAVE_EINVAL;
+  if (plan->batch > 0) return CLEAVE_EINVAL;   // single-GEMM plans only
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
   if (lda < (transA ? plan->M : plan->K) || ldb < (transB ? plan->K : plan->N)) return CLEAVE_EINVAL;

@@ -234,10 +234,14 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
     const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * TN;
     const int k_len = static_cast<int>(task.k_len);
 
-    const unsigned char* a_ptr = static_cast<const unsigned char*>(args.A) +
-                                 (m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * EB;
-    const unsigned char* b_ptr = static_cast<const unsigned char*>(args.B) +
-                                 (n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * EB;
+    const unsigned char* a_ptr =
+        static_cast<const unsigned char*>(args.A) +
+        (batch_offset(task.gemm_id, args.batch_inner, args.a_outer, args.a_inner) + m_base * a_rs +
+         static_cast<int64_t>(task.k0) * a_ks) * EB;
+    const unsigned char* b_ptr =
+        static_cast<const unsigned char*>(args.B) +
+        (batch_offset(task.gemm_id, args.batch_inner, args.b_outer, args.b_inner) + n_base * b_rs +
+         static_cast<int64_t>(task.k0) * b_ks) * EB;
 
     f32x16 acc[MB][NB];
 #pragma unroll

@@ -216,9 +216,11 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     c.n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
     c.steps = static_cast<int>(task.k_len) / S::BK;
     c.a_ptr = static_cast<const unsigned char*>(args.A) +
-              (m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * 2;
+              (batch_offset(task.gemm_id, args.batch_inner, args.a_outer, args.a_inner) +
+               m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * 2;
     c.b_ptr = static_cast<const unsigned char*>(args.B) +
-              (n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
+              (batch_offset(task.gemm_id, args.batch_inner, args.b_outer, args.b_inner) +
+               n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
     c.ldp = task.n_len;
     c.out = args.partials + task.partial_off + static_cast<int64_t>(sub_m) * TM * c.ldp + sub_n * TN;
     return c;

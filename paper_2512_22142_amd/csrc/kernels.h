@@ -18,7 +18,19 @@ struct ExecuteArgs {
   int64_t lda, ldb;           // elements
   int transA, transB;
   float* partials;
+  // Batched plans (batch_inner > 0): task.gemm_id = o * batch_inner + i selects
+  // the operands at element offsets o * outer + i * inner from A and B.
+  uint32_t batch_inner;
+  int64_t a_outer, a_inner, b_outer, b_inner;
 };
+
+// Element offset of the operands of batch member `gemm_id` (0 for plain plans).
+__host__ __device__ inline int64_t batch_offset(uint32_t gemm_id, uint32_t batch_inner, int64_t outer,
+                                                int64_t inner) {
+  if (batch_inner == 0) return 0;
+  const uint32_t o = gemm_id / batch_inner;
+  return static_cast<int64_t>(o) * outer + static_cast<int64_t>(gemm_id - o * batch_inner) * inner;
+}
 
 // Enqueues the execute kernel for one tile class.  `vec` selects the 16-byte
 // load path (caller has checked alignment and divisibility).
@@ -42,6 +54,8 @@ struct ReduceArgs {
   const float* partials;
   void* C;
   int64_t ldc;                // elements
+  uint32_t batch_inner;       // as in ExecuteArgs; offsets apply to C
+  int64_t c_outer, c_inner;
 };
 
 // Enqueues the aggregation kernel.  `vec` selects the float4 path.

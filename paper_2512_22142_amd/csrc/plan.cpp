@@ -44,7 +44,7 @@ void order_work_items(cleave_plan* p) {
     const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
     const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
     struct Key {
-      uint32_t split, m, n;
+      uint32_t member, split, m, n;   // member: 0 unless the plan is a batch
       WorkItem item;
     };
     std::vector<Key> lists[kXcds];
@@ -58,11 +58,15 @@ void order_work_items(cleave_plan* p) {
       // relative position of the chunk inside [0, K): tiles with different
       // split counts still line up by where in K they work
       const uint32_t split = static_cast<uint32_t>(static_cast<uint64_t>(t.k0) * 64 / static_cast<uint64_t>(p->K));
-      lists[rm * gn + rn].push_back(Key{split, m, n, w});
+      // Batch members share no operands: a member stays on one XCD
+      // (member g on XCD g mod 8), members one after the other.
+      const int region = p->batch > 0 ? static_cast<int>(t.gemm_id % kXcds) : rm * gn + rn;
+      lists[region].push_back(Key{t.gemm_id, split, m, n, w});
     }
     size_t longest = 0;
     for (auto& l : lists) {
       std::stable_sort(l.begin(), l.end(), [](const Key& a, const Key& b) {
+        if (a.member != b.member) return a.member < b.member;
         if (a.split != b.split) return a.split < b.split;
         if (a.m != b.m) return a.m < b.m;
         return a.n < b.n;
@@ -98,15 +102,19 @@ void order_work_items(cleave_plan* p) {
 
 // Emits the task records of `tiles` in canonical order and fills the derived
 // tables.  Returns a status code.
+// With n_batch > 0 the tile list is emitted n_batch times, once per batch
+// member g, with gemm_id = g (tile ids restart, partial offsets run on).
 int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles, uint32_t gemm_id,
-                cleave_plan** out) {
+                cleave_plan** out, int64_t n_batch = 0) {
   cleave_plan* p = new (std::nothrow) cleave_plan;
   if (!p) return CLEAVE_ENOMEM;
   try {
+    const uint64_t copies = n_batch > 0 ? static_cast<uint64_t>(n_batch) : 1;
     p->M = M;
     p->N = N;
     p->K = K;
-    p->num_tiles = static_cast<int64_t>(tiles.size());
+    p->batch = n_batch;
+    p->num_tiles = static_cast<int64_t>(tiles.size() * copies);
     uint64_t off = 0;
     uint32_t tile_id = 0;
     // Task, tile and sub-tile indices are 32-bit in the task record and the
@@ -126,7 +134,14 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
         return CLEAVE_EINVAL;
       }
     }
+    if (n_tasks > kMaxIndex / copies || off > kMaxElems / copies) {
+      delete p;
+      return CLEAVE_EINVAL;
+    }
     off = 0;
+    for (uint64_t g = 0; g < copies; ++g) {
+    if (n_batch > 0) gemm_id = static_cast<uint32_t>(g);
+    tile_id = 0;
     for (const Tile& tl : tiles) {
       const int64_t S = tl.ksplit;
       const int64_t kc = (K + S - 1) / S;
@@ -147,6 +162,7 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
         p->tasks.push_back(t);
       }
       ++tile_id;
+    }
     }
     p->partial_elems = static_cast<int64_t>(off);
 
@@ -222,6 +238,25 @@ extern "C" int cleave_plan_uniform(int64_t M, int64_t N, int64_t K, int64_t tile
   return cleave::finish_plan(M, N, K, tiles, gemm_id, out);
 }
 
+extern "C" int cleave_plan_batched(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
+                                   int32_t ksplit, int64_t n_batch, cleave_plan** out) {
+  if (!out) return CLEAVE_EINVAL;
+  if (M < 1 || N < 1 || K < 1 || tile_m < 1 || tile_n < 1 || n_batch < 1) return CLEAVE_EINVAL;
+  if (M > cleave::kMaxDim || N > cleave::kMaxDim || K > cleave::kMaxDim ||
+      n_batch > cleave::kMaxDim)
+    return CLEAVE_EINVAL;
+  if (!cleave::valid_split(K, ksplit)) return CLEAVE_EINVAL;
+  std::vector<Tile> tiles;
+  try {
+    for (int64_t m0 = 0; m0 < M; m0 += tile_m)
+      for (int64_t n0 = 0; n0 < N; n0 += tile_n)
+        tiles.push_back(Tile{m0, std::min(tile_m, M - m0), n0, std::min(tile_n, N - n0), ksplit});
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  return cleave::finish_plan(M, N, K, tiles, 0, out, n_batch);
+}
+
 extern "C" int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_bands,
                                     const int64_t* band_h, const int32_t* n_cols,
                                     const int64_t* col_w, const int32_t* ksplit_per_tile,
@@ -293,4 +328,4 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
-extern "C" int cleave_version(void) { return 101; }
+extern "C" int cleave_version(void) { return 102; }

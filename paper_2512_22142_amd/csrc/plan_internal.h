@@ -93,6 +93,7 @@ struct cleave_plan {
   int64_t M = 0, N = 0, K = 0;
   int64_t partial_elems = 0;
   int64_t num_tiles = 0;
+  int64_t batch = 0;         // > 0: a batch of that many M x N x K GEMMs, task.gemm_id = member
   bool all_k_mult8 = true;   // every k0 and k_len is a multiple of 8
   bool all_k_mult4 = true;
   bool all_klen_mult32 = true;  // every k_len is a multiple of 32

@@ -93,7 +93,8 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args) {
     const float* p0 = args.partials + task.partial_off + static_cast<uint64_t>(item.row0) * n_len;
     const uint32_t count = item.rows * n_len;
     const int64_t c_row0 = static_cast<int64_t>(task.m0) + item.row0;
-    const int64_t c_base = c_row0 * args.ldc + task.n0;
+    const int64_t c_base = batch_offset(task.gemm_id, args.batch_inner, args.c_outer, args.c_inner) +
+                           c_row0 * args.ldc + task.n0;
 
     if constexpr (VEC) {
       switch (S) {

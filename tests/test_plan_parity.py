@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(cleave.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
-    assert cleave.version() == 101
+    assert cleave.version() == 102
     assert cleave.TASK_DTYPE.itemsize == planner.TASK_DTYPE.itemsize == 64
 
 
@@ -124,3 +124,20 @@ def test_null_arguments_are_errors_not_crashes():
     assert lib.cleave_reduce(None, None, None, 0, 0, None) == -1
     lib.cleave_strerror.restype = ctypes.c_char_p
     assert lib.cleave_strerror(-1) == b"invalid argument"
+
+
+@pytest.mark.parametrize("args", [(20, 12, 16, 8, 8, 2, 5), (1024, 1024, 128, 512, 512, 1, 128),
+                                  (7, 5, 6, 3, 2, 3, 1), (192, 192, 64, 128, 128, 1, 6)])
+def test_batched_plan_matches_oracle_bytes(args):
+    tasks, elems = planner.plan_batched(*args)
+    p = cleave.plan_batched(*args)
+    assert p.tasks.tobytes() == tasks.tobytes()
+    assert p.num_tasks == len(tasks) and p.partial_elems == elems
+    assert (p.M, p.N, p.K) == args[:3]
+
+
+def test_batched_plan_rejects_empty_batch_and_bad_split():
+    for args in [(8, 8, 8, 4, 4, 1, 0), (8, 8, 4, 4, 4, 5, 2), (0, 8, 8, 4, 4, 1, 2)]:
+        with pytest.raises(cleave.CleaveError) as e:
+            cleave.plan_batched(*args)
+        assert e.value.status == -1
