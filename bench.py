@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
+    ap.add_argument("--no-attention", action="store_true", help="skip the batched attention-product leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
@@ -256,6 +257,66 @@ def main():
             "bytes_per_call_avg": sum(ver_bytes) / len(gemms),
             "tasks_accepted": accepted, "tasks": sum(p.num_tasks for _, p, _, _ in gemms),
             "note": "blocks written by execute, tol 1e-6; not part of the timed step",
+        }
+
+    # ---- attention products of the same layer as one batched task list each --
+    # (outside the timed step; reported on its own).  4 sequences x 32 heads of
+    # 1024 x 128 x 1024 score GEMMs for c3, then P V; K = 128 cannot be split.
+    if not args.no_attention and args.config in ("c3", "c5"):
+        T = cfg.gemms[0].M
+        hidden = cfg.gemms[0].K
+        s_len, d = 1024, 128
+        n_seq, H = T // s_len, hidden // d
+        G = n_seq * H
+        gen = torch.Generator(device="cpu")
+        gen.manual_seed(cfg.seed + 17)
+        Q, Kt, V = (torch.randn((T, hidden), generator=gen, dtype=torch.float32).to(torch.bfloat16).cuda()
+                    for _ in range(3))
+        ld = hidden
+        tile = cfg.tile_m
+        sp = cleave.plan_batched(s_len, s_len, d, tile, tile, 1, G)
+        pv = cleave.plan_batched(s_len, d, s_len, tile, d, cfg.ksplit, G)
+        sp.upload()
+        pv.upload()
+        ws = workspace[:max(sp.partial_elems, pv.partial_elems)] if workspace.numel() >= max(
+            sp.partial_elems, pv.partial_elems) else torch.empty(max(sp.partial_elems, pv.partial_elems),
+                                                                 dtype=torch.float32, device="cuda")
+        P = torch.empty((G * s_len, s_len), dtype=torch.bfloat16, device="cuda")
+        O = torch.empty((T, hidden), dtype=torch.float32, device="cuda")
+        legs = [
+            ("scores.execute", lambda: cleave.execute_batched(sp, Q, (s_len * ld, d), Kt, (s_len * ld, d), H, ws, 0, 1),
+             2.0 * G * s_len * s_len * d, 2 * T * hidden * 2 + sp.partial_elems * 4),
+            ("scores.reduce", lambda: cleave.reduce_batched(sp, ws, P, (H * s_len * s_len, s_len * s_len), H),
+             0.0, sp.partial_elems * 4 + G * s_len * s_len * 2),
+            ("pv.execute", lambda: cleave.execute_batched(pv, P, (H * s_len * s_len, s_len * s_len), V, (s_len * ld, d), H, ws, 0, 0),
+             2.0 * G * s_len * s_len * d, G * s_len * s_len * 2 + T * hidden * 2 + pv.partial_elems * 4),
+            ("pv.reduce", lambda: cleave.reduce_batched(pv, ws, O, (s_len * ld, d), H),
+             0.0, pv.partial_elems * 4 + T * hidden * 4),
+        ]
+        reps = max(5, args.steps)
+        att = []
+        for name, fn, fl, by in legs:
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            att.append({"leg": name, "ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
+                        "gbps": round(by / ms / 1e6, 1), "algorithmic_bytes": by})
+        tot_ms = sum(a["ms"] for a in att)
+        tot_by = sum(a["algorithmic_bytes"] for a in att)
+        result["attention_roofline"] = {
+            "workload": "%d score GEMMs %dx%dx%d (S=1) and %d P.V GEMMs %dx%dx%d (S=%d), batched task lists, "
+                        "bf16 scores" % (G, s_len, d, s_len, G, s_len, s_len, d, cfg.ksplit),
+            "bound": "hbm", "achieved": round(tot_by / tot_ms / 1e6, 1), "peak": PEAK_HBM_GBPS,
+            "unit": "GB/s", "frac": round(tot_by / tot_ms / 1e6 / PEAK_HBM_GBPS, 4), "traffic": None,
+            "ms": round(tot_ms, 4), "tflops": round(4.0 * G * s_len * s_len * d / tot_ms / 1e9, 1),
+            "legs": att, "kernels": [sp.last_kernel, pv.last_kernel],
+            "note": "fp32 partial blocks make these products output-bound: 64 flop per partial byte",
         }
 
     # ---- CPU baseline: the oracle as it stands, bounded sample -------------
