@@ -32,9 +32,9 @@ PEAK_HBM_GBPS = 8000.0
 # digest below is checked at run time and the figures are dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "290eb68c76dc8e29235d55ed45c460ce7672d0fe4abda30591fbb36ede67dcf6",
-    "execute_bytes_per_launch": (2.0 * 276394 + 396349) * 1024,
-    "reduce_bytes_per_launch": (2.0 * 194451 + 97134) * 1024,
+    "sources_sha256": "956b2f3ad3329570a95d0c67eff91fc3fda49d23d40c28cf4185932420b77099",
+    "execute_bytes_per_launch": (2.0 * 274917 + 396520) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194457 + 97134) * 1024,
 }
 
 
