@@ -175,6 +175,31 @@ int cleave_reduce_batched(cleave_plan* plan, const float* partials, void* C, int
                           int64_t c_outer, int64_t c_inner, int64_t n_inner,
                           int out_dtype, void* hip_stream);
 
+/* ---- aggregation feeding a PS-side streaming operator ---------------------
+ * The paper keeps non-GEMM operators and the optimizer on the parameter
+ * server (Sec. 4.1) and runs the optimizer per weight matrix right behind that
+ * matrix's gradient GEMM (Sec. 6, "Optimizer step accounting and pipelining").
+ * Both calls compute the same fixed-order sum as cleave_reduce and hand it to
+ * the operator without storing it.  Single-GEMM plans only.
+ *
+ * cleave_reduce_residual: C = sum + R.  R: device, M x N, element type and
+ * leading dimension of C; R == C (in-place accumulation) is allowed. */
+int cleave_reduce_residual(cleave_plan* plan, const float* partials, const void* R, void* C,
+                           int64_t ldc, int out_dtype, void* hip_stream);
+
+/* cleave_reduce_adam: the sum is the gradient g of an M x N weight; per element
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   w = w - lr ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay w )
+ * in fp32 (Adam as published, decoupled weight decay).  w, m, v: device fp32,
+ * M x N, leading dimension ld, updated in place; w_bf16: device bf16 copy of
+ * the new weight, same layout, or NULL.  step counts from 1.  Memory traffic
+ * per parameter: 4 S bytes of partials + 24 (+2) bytes of state -- the 26
+ * bytes per parameter of the paper's optimizer term.
+ * CLEAVE_EINVAL: NULL w/m/v, step < 1, beta outside [0, 1), negative eps, NaN. */
+int cleave_reduce_adam(cleave_plan* plan, const float* partials, float* w, float* m, float* v,
+                       void* w_bf16, int64_t ld, float lr, float beta1, float beta2, float eps,
+                       float weight_decay, int64_t step, void* hip_stream);
+
 /* ---- verify --------------------------------------------------------------
  * Check of returned partial blocks by random projection (paper Sec. 6,
  * "Robustness to poisoning attacks": r^T (A B) s = (A^T r)^T (B s), matrix-

@@ -35,7 +35,7 @@ EXPORTS = (
     "cleave_plan_dims", "cleave_plan_upload", "cleave_plan_destroy", "cleave_execute",
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
-    "cleave_reduce_batched",
+    "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
 )
 
 
@@ -86,6 +86,11 @@ def _load():
     lib.cleave_execute_batched.restype = ctypes.c_int
     lib.cleave_reduce_batched.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p]
     lib.cleave_reduce_batched.restype = ctypes.c_int
+    lib.cleave_reduce_residual.argtypes = [p, p, p, p, i64, ctypes.c_int, p]
+    lib.cleave_reduce_residual.restype = ctypes.c_int
+    f32 = ctypes.c_float
+    lib.cleave_reduce_adam.argtypes = [p, p, p, p, p, p, i64, f32, f32, f32, f32, f32, i64, p]
+    lib.cleave_reduce_adam.restype = ctypes.c_int
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
@@ -272,6 +277,40 @@ def reduce_batched(plan, partials, C, c_strides, n_inner, stream=None):
     _check(_lib.cleave_reduce_batched(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
                                       int(c_strides[0]), int(c_strides[1]), int(n_inner),
                                       _dtype_code(C), _stream_ptr(stream)), "cleave_reduce_batched")
+
+
+def reduce_residual(plan, partials, R, C, stream=None):
+    """cleave_reduce_residual: C = sum of partials + R (R may be C)."""
+    c_ptr, ldc = _matrix(C, "C")
+    r_ptr, ldr = _matrix(R, "R")
+    if tuple(C.shape) != (plan.M, plan.N) or tuple(R.shape) != (plan.M, plan.N) or ldr != ldc \
+            or R.dtype != C.dtype:
+        raise ValueError("R and C must be M x N with the same dtype and leading dimension")
+    _check(_lib.cleave_reduce_residual(plan._h, ctypes.c_void_p(partials.data_ptr()), r_ptr, c_ptr,
+                                       ldc, _dtype_code(C), _stream_ptr(stream)),
+           "cleave_reduce_residual")
+
+
+def reduce_adam(plan, partials, w, m, v, lr, beta1, beta2, eps, weight_decay, step, w_bf16=None,
+                stream=None):
+    """cleave_reduce_adam: Adam update of the M x N fp32 weight w (moments m, v)
+    with the aggregated partials as gradient; optional bf16 copy of the result."""
+    import torch
+    w_ptr, ld = _matrix(w, "w")
+    ptrs = []
+    for t, what, dt in ((m, "m", torch.float32), (v, "v", torch.float32), (w_bf16, "w_bf16", torch.bfloat16)):
+        if t is None and what == "w_bf16":
+            ptrs.append(None)
+            continue
+        q, l = _matrix(t, what)
+        if t.dtype != dt or tuple(t.shape) != (plan.M, plan.N) or l != ld:
+            raise ValueError("%s must be M x N %s with w's leading dimension" % (what, dt))
+        ptrs.append(q)
+    if w.dtype != torch.float32 or tuple(w.shape) != (plan.M, plan.N):
+        raise ValueError("w must be an M x N fp32 device tensor")
+    _check(_lib.cleave_reduce_adam(plan._h, ctypes.c_void_p(partials.data_ptr()), w_ptr, ptrs[0],
+                                   ptrs[1], ptrs[2], ld, lr, beta1, beta2, eps, weight_decay,
+                                   int(step), _stream_ptr(stream)), "cleave_reduce_adam")
 
 
 def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=None,

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <limits>
 #include <map>
@@ -296,8 +297,15 @@ extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids
 
 namespace {
 
+// Which operator consumes the aggregated values.
+struct ReduceEpilogue {
+  const void* residual = nullptr;          // C = sum + residual
+  const cleave::AdamArgs* adam = nullptr;  // Adam update of adam->w (C unused)
+};
+
 int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, int out_dtype,
-                int64_t n_inner, int64_t c_outer, int64_t c_inner, void* hip_stream) {
+                int64_t n_inner, int64_t c_outer, int64_t c_inner, void* hip_stream,
+                const ReduceEpilogue& epi = ReduceEpilogue{}) {
   if (!plan || !partials || !C) return CLEAVE_EINVAL;
   if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if (ldc < plan->N) return CLEAVE_EINVAL;
@@ -311,8 +319,12 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   rc = compute_units(&cus);
   if (rc != CLEAVE_OK) return rc;
 
-  const bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
-                   c_outer % 4 == 0 && c_inner % 4 == 0;
+  bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
+             c_outer % 4 == 0 && c_inner % 4 == 0;
+  if (epi.residual) vec = vec && aligned(epi.residual, 4 * ob);
+  if (epi.adam)
+    vec = vec && aligned(epi.adam->m, 16) && aligned(epi.adam->v, 16) &&
+          (!epi.adam->w_bf16 || aligned(epi.adam->w_bf16, 8));
   cleave::ReduceArgs args{};
   args.tasks = plan->d_tasks;
   args.items = plan->d_reduce_items;
@@ -324,11 +336,54 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   args.c_outer = c_outer;
   args.c_inner = c_inner;
   const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20)); (void)cus;
-  CLEAVE_HIP(cleave::launch_reduce(args, out_dtype, vec, grid, stream));
+  if (epi.adam) {
+    CLEAVE_HIP(cleave::launch_reduce_adam(args, *epi.adam, vec, grid, stream));
+  } else if (epi.residual) {
+    CLEAVE_HIP(cleave::launch_reduce_residual(args, epi.residual, out_dtype, vec, grid, stream));
+  } else {
+    CLEAVE_HIP(cleave::launch_reduce(args, out_dtype, vec, grid, stream));
+  }
   return CLEAVE_OK;
 }
 
 }  // namespace
+
+extern "C" int cleave_reduce_residual(cleave_plan* plan, const float* partials, const void* R,
+                                      void* C, int64_t ldc, int out_dtype, void* hip_stream) {
+  if (!R || (plan && plan->batch > 0)) return CLEAVE_EINVAL;
+  if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  if (!aligned(R, out_dtype == CLEAVE_BF16 ? 2 : 4)) return CLEAVE_EINVAL;
+  ReduceEpilogue epi;
+  epi.residual = R;
+  return reduce_impl(plan, partials, C, ldc, out_dtype, 0, 0, 0, hip_stream, epi);
+}
+
+extern "C" int cleave_reduce_adam(cleave_plan* plan, const float* partials, float* w, float* m,
+                                  float* v, void* w_bf16, int64_t ld, float lr, float beta1,
+                                  float beta2, float eps, float weight_decay, int64_t step,
+                                  void* hip_stream) {
+  if (!w || !m || !v || (plan && plan->batch > 0)) return CLEAVE_EINVAL;
+  if (step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) ||
+      !(eps >= 0.0f) || !(lr == lr) || !(weight_decay == weight_decay))
+    return CLEAVE_EINVAL;
+  if (!aligned(m, 4) || !aligned(v, 4) || !aligned(w_bf16, 2)) return CLEAVE_EINVAL;
+  cleave::AdamArgs h{};
+  h.w = w;
+  h.m = m;
+  h.v = v;
+  h.w_bf16 = static_cast<uint16_t*>(w_bf16);
+  h.lr = lr;
+  h.beta1 = beta1;
+  h.beta2 = beta2;
+  h.eps = eps;
+  h.weight_decay = weight_decay;
+  h.inv_bias1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step))));
+  h.inv_bias2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step))));
+  ReduceEpilogue epi;
+  epi.adam = &h;
+  // the fp32 master weight takes C's place in the common checks (pointer, leading dimension)
+  return reduce_impl(plan, partials, w, ld, CLEAVE_F32, 0, 0, 0, hip_stream, epi);
+}
 
 extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
                              int out_dtype, void* hip_stream) {

@@ -62,6 +62,24 @@ struct ReduceArgs {
 hipError_t launch_reduce(const ReduceArgs& args, int out_dtype, bool vec, int grid,
                          hipStream_t stream);
 
+// Aggregation with a residual added: C = sum of partials + R; R has C's
+// element type, leading dimension and batch strides.
+hipError_t launch_reduce_residual(const ReduceArgs& args, const void* R, int out_dtype, bool vec,
+                                  int grid, hipStream_t stream);
+
+// Aggregation feeding an Adam update of the weight whose gradient the sum is
+// (ReduceArgs::C unused; w, m, v, w_bf16 share ldc and the batch strides).
+struct AdamArgs {
+  float* w;
+  float* m;
+  float* v;
+  uint16_t* w_bf16;   // may be null
+  float lr, beta1, beta2, eps, weight_decay;
+  float inv_bias1, inv_bias2;   // 1 / (1 - beta^step)
+};
+hipError_t launch_reduce_adam(const ReduceArgs& args, const AdamArgs& h, bool vec, int grid,
+                              hipStream_t stream);
+
 // ---- returned-block check ---------------------------------------------------
 
 // Projection of a stored operand onto a weight vector, once per segment:

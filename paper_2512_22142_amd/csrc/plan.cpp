@@ -328,4 +328,4 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
-extern "C" int cleave_version(void) { return 102; }
+extern "C" int cleave_version(void) { return 103; }
