@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
     ap.add_argument("--no-attention", action="store_true", help="skip the batched attention-product leg")
+    ap.add_argument("--no-epilogues", action="store_true", help="skip the fused Adam / residual leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
@@ -317,6 +318,62 @@ def main():
             "ms": round(tot_ms, 4), "tflops": round(4.0 * G * s_len * s_len * d / tot_ms / 1e9, 1),
             "legs": att, "kernels": [sp.last_kernel, pv.last_kernel],
             "note": "fp32 partial blocks make these products output-bound: 64 flop per partial byte",
+        }
+
+    # ---- PS-side streaming operators fused into the aggregation --------------
+    # (outside the timed step).  Adam behind every weight-gradient GEMM of the
+    # layer, residual add behind the two projections that feed the residual stream.
+    if not args.no_epilogues:
+        reps = max(5, args.steps)
+        adam_ms, adam_bytes, res_ms, res_bytes = 0.0, 0, 0.0, 0
+        for i, (g, plan, dA, dB) in enumerate(gemms):
+            is_dw = g.name.endswith(".dw")
+            is_res = g.name in ("o.fwd", "down.fwd")
+            if not (is_dw or is_res):
+                continue
+            cleave.execute(plan, dA, dB, slots[i], g.transA, g.transB)
+            if is_dw:
+                w = torch.zeros((g.M, g.N), dtype=torch.float32, device="cuda").normal_(0, 0.02)
+                m = torch.zeros_like(w)
+                v = torch.zeros_like(w)
+                w16 = torch.empty((g.M, g.N), dtype=torch.bfloat16, device="cuda")
+                state = {"t": 0}
+
+                def fn():
+                    state["t"] += 1
+                    cleave.reduce_adam(plan, slots[i], w, m, v, 1e-4, 0.9, 0.95, 1e-8, 0.1, state["t"], w_bf16=w16)
+                nbytes = plan.partial_elems * 4 + g.M * g.N * 26
+            else:
+                resid = torch.zeros((g.M, g.N), dtype=torch.float32, device="cuda").normal_()
+                out = torch.empty_like(resid)
+
+                def fn():
+                    cleave.reduce_residual(plan, slots[i], resid, out)
+                nbytes = plan.partial_elems * 4 + g.M * g.N * 8
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            if is_dw:
+                adam_ms += ms
+                adam_bytes += nbytes
+            else:
+                res_ms += ms
+                res_bytes += nbytes
+            del fn
+        result["epilogue_roofline"] = {
+            "kernel": "reduce with fused Adam (7 weight-gradient GEMMs) / fused residual add (o.fwd, down.fwd)",
+            "bound": "hbm", "achieved": round(adam_bytes / adam_ms / 1e6, 1), "peak": PEAK_HBM_GBPS,
+            "unit": "GB/s", "frac": round(adam_bytes / adam_ms / 1e6 / PEAK_HBM_GBPS, 4), "traffic": None,
+            "adam_ms_per_layer": round(adam_ms, 4), "adam_bytes_per_param": 26 + 4 * cfg.ksplit,
+            "residual_ms": round(res_ms, 4), "residual_gbps": round(res_bytes / res_ms / 1e6, 1),
+            "note": "bytes = 4*S per element of partials + 26 per parameter (fp32 w, m, v read and written, "
+                    "bf16 copy written); the gradient is never stored",
         }
 
     # ---- CPU baseline: the oracle as it stands, bounded sample -------------
