@@ -32,9 +32,9 @@ PEAK_HBM_GBPS = 8000.0
 # digest below is checked at run time and the figures are dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "956b2f3ad3329570a95d0c67eff91fc3fda49d23d40c28cf4185932420b77099",
-    "execute_bytes_per_launch": (2.0 * 274917 + 396520) * 1024,
-    "reduce_bytes_per_launch": (2.0 * 194457 + 97134) * 1024,
+    "sources_sha256": "66972d94a946e611f0a22616fb1e5814d20a60c655f782f9d345937daf6774dc",
+    "execute_bytes_per_launch": (2.0 * 276136 + 396520) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194456 + 97134) * 1024,
 }
 
 
