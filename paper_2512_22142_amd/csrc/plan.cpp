@@ -26,6 +26,19 @@ bool valid_split(int64_t K, int64_t S) {
 
 constexpr int kXcds = 8;
 
+// The work items that run on an XCD at the same time (one per CU, 32 CUs) are
+// taken from a patch of kPatchRows x kPatchCols sub-tiles at one chunk of the
+// inner dimension: they share that many row panels of A and column panels of
+// B in the XCD's L2.
+#ifndef CLEAVE_PATCH_ROWS
+#define CLEAVE_PATCH_ROWS 4
+#endif
+#ifndef CLEAVE_PATCH_COLS
+#define CLEAVE_PATCH_COLS 8
+#endif
+constexpr uint32_t kPatchRows = CLEAVE_PATCH_ROWS;
+constexpr uint32_t kPatchCols = CLEAVE_PATCH_COLS;
+
 void order_work_items(cleave_plan* p) {
   // Region grid: minimise M/gm + N/gn over gm * gn = 8.
   int gm = 1, gn = kXcds;
@@ -44,7 +57,7 @@ void order_work_items(cleave_plan* p) {
     const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
     const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
     struct Key {
-      uint32_t member, split, m, n;   // member: 0 unless the plan is a batch
+      uint32_t member, split, pm, pn, m, n;   // member: 0 unless the plan is a batch
       WorkItem item;
     };
     std::vector<Key> lists[kXcds];
@@ -61,13 +74,15 @@ void order_work_items(cleave_plan* p) {
       // Batch members share no operands: a member stays on one XCD
       // (member g on XCD g mod 8), members one after the other.
       const int region = p->batch > 0 ? static_cast<int>(t.gemm_id % kXcds) : rm * gn + rn;
-      lists[region].push_back(Key{t.gemm_id, split, m, n, w});
+      lists[region].push_back(Key{t.gemm_id, split, m / (kPatchRows * tr), n / (kPatchCols * tc), m, n, w});
     }
     size_t longest = 0;
     for (auto& l : lists) {
       std::stable_sort(l.begin(), l.end(), [](const Key& a, const Key& b) {
         if (a.member != b.member) return a.member < b.member;
         if (a.split != b.split) return a.split < b.split;
+        if (a.pm != b.pm) return a.pm < b.pm;
+        if (a.pn != b.pn) return a.pn < b.pn;
         if (a.m != b.m) return a.m < b.m;
         return a.n < b.n;
       });
