@@ -1,0 +1,135 @@
+"""Pins for the oracle of the cost model (Sec. 4.1) and of the shard
+assignment built on it: hand-computed costs with each term dominating in turn,
+the cache-aware downlink term of churn recovery (Sec. 4.2), the memory and
+zero-task constraints, coverage of the output, the closed-form optimum of a
+homogeneous compute-bound fleet, and brute force over all guillotine layouts on
+tiny instances."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import planner
+from oracle import scheduler as sc
+
+
+def dev(dl=100.0, ul=50.0, ldl=1.0, lul=2.0, F=1000.0, mem=1e18):
+    return sc.Device(dl, ul, ldl, lul, F, mem)
+
+
+def test_cost_terms_by_hand():
+    # alpha=3, beta=4, n=5, b=2: downlink bytes 30+40, uplink bytes 24, flops 120
+    assert sc.shard_cost(dev(), 3, 4, 5, 2) == 24 / 50 + 2               # uplink dominates: 2.48
+    assert sc.shard_cost(dev(lul=0.0), 3, 4, 5, 2) == 70 / 100 + 1       # downlink: 1.7
+    assert sc.shard_cost(dev(ldl=0.0, lul=0.0, F=10.0), 3, 4, 5, 2) == 12.0   # compute: 120 / 10
+    assert sc.shard_cost(dev(), 0, 0, 5, 2) == 0.0                       # idle device
+    for bad in [(0, 3), (2, 0), (-1, 2)]:
+        with pytest.raises(ValueError):
+            sc.shard_cost(dev(), bad[0], bad[1], 5, 2)
+
+
+def test_cached_rows_and_columns_are_not_downloaded_again():
+    d = dev(lul=0.0, ul=1e9, ldl=0.0, F=1e9)
+    assert sc.shard_cost(d, 3, 4, 5, 2) == 70 / 100
+    assert sc.shard_cost(d, 3, 4, 5, 2, alpha_fetch=0) == 40 / 100       # rows cached
+    assert sc.shard_cost(d, 3, 4, 5, 2, alpha_fetch=1, beta_fetch=0) == 10 / 100
+    # compute and uplink still see the whole shard
+    assert sc.shard_cost(dev(F=10.0), 3, 4, 5, 2, alpha_fetch=0, beta_fetch=0) == 12.0
+
+
+def test_memory_constraint_counts_rows_columns_and_output():
+    assert sc.shard_fits(dev(mem=94), 3, 4, 5, 2)        # 30 + 40 + 24
+    assert not sc.shard_fits(dev(mem=93), 3, 4, 5, 2)
+
+
+def check_layout(m, q, n, b, devs, g, res):
+    band_h, col_w, owner, cost = res
+    assert sum(band_h) == m and all(sum(w) == q for w in col_w)
+    used = [k for row in owner for k in row]
+    assert len(used) == len(set(used))                   # one shard per device
+    worst = 0.0
+    for h, widths, owners in zip(band_h, col_w, owner):
+        for w, k in zip(widths, owners):
+            assert h >= 1 and w >= 1 and sc.shard_fits(devs[k], h, w, n, b)
+            worst = max(worst, sc.shard_cost(devs[k], h, w, n, b))
+    assert cost == worst
+    tasks, elems = planner.plan_explicit(m, q, n, band_h, col_w, [1] * len(used))
+    planner.check_plan_invariants(tasks, m, q, n)        # exact cover, no empty task
+    assert elems == m * q
+
+
+def test_homogeneous_compute_bound_fleet_reaches_the_even_split():
+    n, F = 512, 1e12
+    fleet = [sc.Device(1e30, 1e30, 0.0, 0.0, F, 1e30) for _ in range(4)]
+    res = sc.assign(256, 256, n, 2, fleet, 64)
+    check_layout(256, 256, n, 2, fleet, 64, res)
+    assert res[0] == [128, 128] and res[1] == [[128, 128], [128, 128]]
+    assert res[3] == 2.0 * 128 * 128 * n / F
+    # nine devices, 3 x 3 grid of a 384 x 384 output
+    fleet = [sc.Device(1e30, 1e30, 0.0, 0.0, F, 1e30) for _ in range(9)]
+    res = sc.assign(384, 384, n, 2, fleet, 128)
+    assert res[0] == [128] * 3 and res[1] == [[128] * 3] * 3
+
+
+def brute_force_optimum(m, q, n, b, devs, g):
+    """Minimum over all guillotine band layouts on the granule grid and all
+    assignments of distinct devices to the tiles."""
+    def compositions(total):
+        if total == 0:
+            yield []
+            return
+        for first in range(1, total + 1):
+            for rest in compositions(total - first):
+                yield [first] + rest
+    best = float("inf")
+    for bands in compositions(m // g):
+        for cols in itertools.product(*[list(compositions(q // g)) for _ in bands]):
+            tiles = [(h * g, w * g) for h, ws in zip(bands, cols) for w in ws]
+            if len(tiles) > len(devs):
+                continue
+            for perm in itertools.permutations(range(len(devs)), len(tiles)):
+                if all(sc.shard_fits(devs[k], h, w, n, b) for (h, w), k in zip(tiles, perm)):
+                    best = min(best, max(sc.shard_cost(devs[k], h, w, n, b) for (h, w), k in zip(tiles, perm)))
+    return best
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_against_brute_force_on_tiny_instances(seed):
+    rng = np.random.default_rng(seed)
+    g, n, b = 8, 32, 2
+    m, q = g * int(rng.integers(1, 4)), g * int(rng.integers(1, 4))
+    devs = [sc.Device(10 ** rng.uniform(2, 4), 10 ** rng.uniform(2, 4), rng.uniform(0, 0.05), rng.uniform(0, 0.05),
+                      10 ** rng.uniform(4, 6), 1e18) for _ in range(int(rng.integers(2, 5)))]
+    res = sc.assign(m, q, n, b, devs, g)
+    check_layout(m, q, n, b, devs, g, res)
+    opt = brute_force_optimum(m, q, n, b, devs, g)
+    assert res[3] >= opt * (1 - 1e-12)          # nothing beats the enumerated optimum
+    assert res[3] <= 2.0 * opt                  # and the heuristic stays within a factor two of it here
+
+
+def test_stronger_device_gets_the_larger_shard_and_weak_ones_may_idle():
+    strong = sc.Device(1e9, 1e9, 0.0, 0.0, 1e13, 1e18)
+    weak = sc.Device(1e6, 1e6, 0.0, 0.0, 1e10, 1e18)
+    res = sc.assign(1024, 1024, 1024, 2, [weak, strong], 64)
+    check_layout(1024, 1024, 1024, 2, [weak, strong], 64, res)
+    area = {}
+    for h, widths, owners in zip(*res[:3]):
+        for w, k in zip(widths, owners):
+            area[k] = h * w
+    assert area[1] > area.get(0, 0)
+    # a device too slow to help within the best time stays idle (zero-task constraint)
+    hopeless = sc.Device(1.0, 1.0, 10.0, 10.0, 1.0, 1e18)
+    res = sc.assign(256, 256, 64, 2, [strong, hopeless], 64)
+    assert [k for row in res[2] for k in row] == [0]
+
+
+def test_memory_limits_shape_the_layout_or_make_it_infeasible():
+    n, b = 256, 2
+    small = [sc.Device(1e9, 1e9, 0.0, 0.0, 1e12, 64 * n * b * 2 + 64 * 64 * b) for _ in range(16)]
+    res = sc.assign(256, 256, n, b, small, 64)           # each device holds at most a 64 x 64 shard
+    check_layout(256, 256, n, b, small, 64, res)
+    assert all(h == 64 for h in res[0]) and all(w == 64 for ws in res[1] for w in ws)
+    with pytest.raises(ValueError):
+        sc.assign(256, 256, n, b, small[:15], 64)        # 15 such devices cannot cover 16 shards
+    with pytest.raises(ValueError):
+        sc.assign(0, 8, 8, 2, small, 8)
