@@ -229,6 +229,51 @@ int cleave_verify(cleave_plan* plan,
                   double* lhs, double* rhs, double* scale, int32_t* accept,
                   void* hip_stream);
 
+/* ---- cost model and shard assignment (host only) -------------------------
+ * Paper Sec. 4.1: a device d receives alpha rows of A (m x n) and beta columns
+ * of B (n x q), b bytes per element, and returns the alpha x beta block:
+ *   downlink (alpha n b + n beta b) / down_bw + down_lat,
+ *   uplink   alpha beta b / up_bw + up_lat,   compute 2 alpha beta n / flops,
+ * overlapped: the shard costs the maximum of the three; it must fit
+ * alpha n b + n beta b + alpha beta b <= mem_bytes; a device is idle
+ * (alpha = beta = 0, cost 0) or has both >= 1; a GEMM costs the maximum over
+ * its devices.  Units: bytes/s, s, flop/s, bytes. */
+typedef struct cleave_device {
+  double down_bw, up_bw;     /* > 0 */
+  double down_lat, up_lat;   /* >= 0 */
+  double flops;              /* > 0 */
+  double mem_bytes;          /* >= 0 */
+} cleave_device;
+
+/* Cost of one shard.  alpha_fetch <= alpha and beta_fetch <= beta are the rows
+ * and columns the device still has to download (Sec. 4.2, churn recovery with
+ * cached rows / columns); pass alpha, beta for a cold start.  Returns a
+ * negative value on invalid arguments (NULL, non-positive rates, one of alpha
+ * and beta zero, sizes above 2^24, elem_bytes above 16). */
+double cleave_shard_cost(const cleave_device* dev, int64_t alpha, int64_t beta,
+                         int64_t alpha_fetch, int64_t beta_fetch, int64_t n, int32_t elem_bytes);
+/* 1 if the shard fits the device's memory, 0 if not, CLEAVE_EINVAL on invalid arguments. */
+int cleave_shard_fits(const cleave_device* dev, int64_t alpha, int64_t beta, int64_t n,
+                      int32_t elem_bytes);
+
+/* Heterogeneous assignment of the m x q output of one GEMM (inner dimension n)
+ * to at most n_devs devices, one shard per device, as a guillotine tiling:
+ * row bands, each cut into columns.  A deterministic heuristic in place of
+ * the paper's MILP (bisection on the target time; devices by descending
+ * capacity; see scheduler.cpp).  Shard edges are multiples of `granule` except
+ * for ragged rests.  Outputs, all host arrays the caller provides with room
+ * for n_devs entries each: *n_bands, band_h[n_bands] (sum m), n_cols[n_bands],
+ * col_w (widths of band 0, then band 1, ...; each band sums to q),
+ * tile_device (same order: index into devs of the tile's owner), *cost = the
+ * GEMM's cost under the model.  band_h / n_cols / col_w are the arguments of
+ * cleave_plan_explicit (with one K-split entry of 1 per tile).
+ * CLEAVE_EINVAL: NULL pointers, invalid device, non-positive or too large
+ * sizes, or no cover exists within the devices' memory. */
+int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                  const cleave_device* devs, int32_t n_devs, int64_t granule,
+                  int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
+                  int32_t* tile_device, double* cost);
+
 /* ---- misc ----------------------------------------------------------------*/
 const char* cleave_strerror(int status);
 /* hipError_t value of the most recent CLEAVE_EHIP on this thread (0 if none). */

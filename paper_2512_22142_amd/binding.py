@@ -36,7 +36,15 @@ EXPORTS = (
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
+    "cleave_shard_cost", "cleave_shard_fits", "cleave_assign",
 )
+
+
+class Device(ctypes.Structure):
+    """cleave_device: bytes/s, s, flop/s, bytes."""
+    _fields_ = [("down_bw", ctypes.c_double), ("up_bw", ctypes.c_double),
+                ("down_lat", ctypes.c_double), ("up_lat", ctypes.c_double),
+                ("flops", ctypes.c_double), ("mem_bytes", ctypes.c_double)]
 
 
 class CleaveError(RuntimeError):
@@ -91,6 +99,12 @@ def _load():
     f32 = ctypes.c_float
     lib.cleave_reduce_adam.argtypes = [p, p, p, p, p, p, i64, f32, f32, f32, f32, f32, i64, p]
     lib.cleave_reduce_adam.restype = ctypes.c_int
+    lib.cleave_shard_cost.argtypes = [p, i64, i64, i64, i64, i64, i32]
+    lib.cleave_shard_cost.restype = ctypes.c_double
+    lib.cleave_shard_fits.argtypes = [p, i64, i64, i64, i32]
+    lib.cleave_shard_fits.restype = ctypes.c_int
+    lib.cleave_assign.argtypes = [i64, i64, i64, i32, p, i32, i64, p, p, p, p, p, p]
+    lib.cleave_assign.restype = ctypes.c_int
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
@@ -343,6 +357,46 @@ def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=No
         vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
         vec(scale, torch.float64, plan.num_tasks, "scale", True),
         vec(accept, torch.int32, plan.num_tasks, "accept"), _stream_ptr(stream)), "cleave_verify")
+
+
+def shard_cost(dev, alpha, beta, n, elem_bytes, alpha_fetch=None, beta_fetch=None):
+    """cleave_shard_cost (host only)."""
+    c = _lib.cleave_shard_cost(ctypes.byref(dev), alpha, beta,
+                               alpha if alpha_fetch is None else alpha_fetch,
+                               beta if beta_fetch is None else beta_fetch, n, elem_bytes)
+    if c < 0:
+        raise CleaveError(EINVAL, "cleave_shard_cost")
+    return c
+
+
+def shard_fits(dev, alpha, beta, n, elem_bytes):
+    rc = _lib.cleave_shard_fits(ctypes.byref(dev), alpha, beta, n, elem_bytes)
+    if rc < 0:
+        raise CleaveError(rc, "cleave_shard_fits")
+    return bool(rc)
+
+
+def assign(m, q, n, elem_bytes, devices, granule):
+    """cleave_assign (host only): returns (band_h, col_w, owner, cost) with one
+    list of column widths and of owning device indices per band."""
+    k = len(devices)
+    devs = (Device * max(k, 1))(*devices)
+    n_bands = ctypes.c_int32()
+    band_h = (ctypes.c_int64 * max(k, 1))()
+    n_cols = (ctypes.c_int32 * max(k, 1))()
+    col_w = (ctypes.c_int64 * max(k, 1))()
+    owner = (ctypes.c_int32 * max(k, 1))()
+    cost = ctypes.c_double()
+    _check(_lib.cleave_assign(m, q, n, elem_bytes, devs, k, granule, ctypes.byref(n_bands), band_h,
+                              n_cols, col_w, owner, ctypes.byref(cost)), "cleave_assign")
+    bands, widths, owners, pos = [], [], [], 0
+    for bnd in range(n_bands.value):
+        c = n_cols[bnd]
+        bands.append(int(band_h[bnd]))
+        widths.append([int(x) for x in col_w[pos:pos + c]])
+        owners.append([int(x) for x in owner[pos:pos + c]])
+        pos += c
+    return bands, widths, owners, cost.value
 
 
 def version():

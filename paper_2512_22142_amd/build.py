@@ -10,11 +10,13 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcleave.so")
 
-SOURCES = ["plan.cpp", "api.cpp", "execute.hip", "execute_direct.hip", "reduce.hip", "verify.hip"]
+SOURCES = ["plan.cpp", "scheduler.cpp", "api.cpp", "execute.hip", "execute_direct.hip", "reduce.hip", "verify.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    # the host-side planners compare doubles the oracle must reproduce: no fused multiply-adds
+    "-Xarch_host", "-ffp-contract=off",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
     # no packed-fp32 instructions in device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -343,4 +343,4 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
-extern "C" int cleave_version(void) { return 103; }
+extern "C" int cleave_version(void) { return 104; }

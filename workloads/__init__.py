@@ -7,4 +7,4 @@ values as plain inputs.
 """
 from .configs import GemmSpec, LayerConfig, layer_config, CONFIG_NAMES  # noqa: F401
 from .tensors import make_tensor, make_gemm_operands, make_probe_vectors  # noqa: F401
-from .hetero import draw_explicit_tiling, draw_reissue  # noqa: F401
+from .hetero import draw_explicit_tiling, draw_reissue, draw_fleet  # noqa: F401

@@ -82,3 +82,31 @@ def draw_reissue(n_tasks, seed, fraction=0.05):
     rng = np.random.default_rng(seed)
     count = max(1, math.ceil(fraction * n_tasks))
     return [int(i) for i in rng.permutation(n_tasks)[:count]]
+
+
+# Device fleet for the cost-model planner: the paper's classes (Sec. 2.1: phones
+# with 512 MB - 1 GB, laptops with 4 - 10 GB usable memory; Sec. 5.1 samples
+# capabilities from public benchmark and speed-test data that are not
+# available here).  Stand-in: log-uniform draws inside per-class ranges.
+FLEET_CLASSES = (
+    # weight, downlink Mbit/s, uplink Mbit/s, latency ms, TFLOP/s, memory GB
+    (0.4, (20, 100), (5, 20), (20, 80), (1, 4), 0.5),
+    (0.3, (50, 300), (10, 50), (15, 60), (2, 8), 1.0),
+    (0.2, (100, 600), (20, 100), (5, 30), (5, 15), 4.0),
+    (0.1, (200, 1000), (50, 300), (2, 20), (10, 30), 10.0),
+)
+
+
+def draw_fleet(n_devices, seed):
+    """Returns a list of (down_bw B/s, up_bw B/s, down_lat s, up_lat s, flop/s, mem bytes)."""
+    rng = np.random.default_rng(seed)
+    weights = [c[0] for c in FLEET_CLASSES]
+    out = []
+    for _ in range(n_devices):
+        c = FLEET_CLASSES[int(rng.choice(len(FLEET_CLASSES), p=weights))]
+
+        def logu(lo_hi):
+            return float(np.exp(rng.uniform(np.log(lo_hi[0]), np.log(lo_hi[1]))))
+        lat = logu(c[3]) * 1e-3
+        out.append((logu(c[1]) * 1e6 / 8, logu(c[2]) * 1e6 / 8, lat, lat, logu(c[4]) * 1e12, c[5] * 1e9))
+    return out
