@@ -29,11 +29,13 @@ PEAK_HBM_GBPS = 8000.0
 # FETCH_SIZE and WRITE_SIZE counter runs summarised under profiles/ (FETCH_SIZE
 # scaled by 2.0, WRITE_SIZE by 1.0: what the same counters read for a plain copy
 # of known size).  Valid only for the kernel sources they were taken with: the
-# digest below is checked at run time and the figures are dropped on a mismatch.
+# digest below (over the files that define the execute and reduce kernels, their
+# arguments and the work-item order) is checked at run time and the figures are
+# dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "66972d94a946e611f0a22616fb1e5814d20a60c655f782f9d345937daf6774dc",
-    "execute_bytes_per_launch": (2.0 * 276136 + 396520) * 1024,
+    "sources_sha256": "0a870d3017dc20ceb2e896c9b3ef50aefd4d865bb15a7fd787cdbf3b5e1f2220",
+    "execute_bytes_per_launch": (2.0 * 246943 + 396520) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194456 + 97134) * 1024,
 }
 
@@ -42,10 +44,9 @@ def kernel_sources_digest():
     import hashlib
     csrc = os.path.join(ROOT, "paper_2512_22142_amd", "csrc")
     h = hashlib.sha256()
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".cpp", ".h")):
-            with open(os.path.join(csrc, name), "rb") as f:
-                h.update(name.encode() + b"\0" + f.read())
+    for name in ("execute.hip", "execute_direct.hip", "kernels.h", "plan.cpp", "plan_internal.h", "reduce.hip"):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()
 
 

@@ -343,4 +343,3 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
-extern "C" int cleave_version(void) { return 104; }
