@@ -160,6 +160,24 @@ int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n
                            const void* B, int64_t ldb, int transB, int64_t b_outer, int64_t b_inner,
                            int64_t n_inner, int dtype, float* partials, void* hip_stream);
 
+/* Execute for plans without K-splits (every task covers the whole inner
+ * dimension, as in the paper's own decomposition, Sec. 4.1): each block is
+ * already the finished piece of the output, so it is written straight to its
+ * place in C and no partial buffer or reduce call is needed (Sec. 3.2: the PS
+ * only assembles the returned blocks).  The values are those cleave_execute
+ * followed by cleave_reduce would give, bit for bit (fp32; bf16 = round to
+ * nearest even of them).  Plain or batched plan: for a plain plan pass
+ * n_inner = 0 and all strides 0; for a batched plan the strides are those of
+ * cleave_execute_batched / cleave_reduce_batched.  C: device, out_dtype
+ * elements, leading dimension ldc >= N.  task_ids as for cleave_execute.
+ * CLEAVE_EINVAL: as for cleave_execute, or a task with a K-split. */
+int cleave_execute_assemble(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                            const void* A, int64_t lda, int transA, int64_t a_outer, int64_t a_inner,
+                            const void* B, int64_t ldb, int transB, int64_t b_outer, int64_t b_inner,
+                            int64_t n_inner, int dtype,
+                            void* C, int64_t ldc, int64_t c_outer, int64_t c_inner, int out_dtype,
+                            void* hip_stream);
+
 /* ---- reduce --------------------------------------------------------------
  * C[m0+i, n0+j] = ((P_0[i,j] + P_1[i,j]) + ...) + P_{S-1}[i,j] for every tile.
  * partials: device fp32, as written by cleave_execute.  C: device, M x N

@@ -10,6 +10,6 @@ include/cleave.h); build it with `python -m paper_2512_22142_amd.build`.
 """
 from .binding import (  # noqa: F401
     BF16, F32, CleaveError, Device, Plan, assign, shard_cost, shard_fits, TASK_DTYPE, EXPORTS, LIB_PATH,
-    execute, execute_batched, plan_batched, plan_explicit, plan_uniform, reduce, reduce_adam, reduce_batched,
+    execute, execute_assemble, execute_batched, plan_batched, plan_explicit, plan_uniform, reduce, reduce_adam, reduce_batched,
     reduce_residual, verify, version,
 )

@@ -36,7 +36,7 @@ EXPORTS = (
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
-    "cleave_shard_cost", "cleave_shard_fits", "cleave_assign",
+    "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_execute_assemble",
 )
 
 
@@ -92,6 +92,10 @@ def _load():
     lib.cleave_execute_batched.argtypes = [p, p, i64, p, i64, ctypes.c_int, i64, i64,
                                            p, i64, ctypes.c_int, i64, i64, i64, ctypes.c_int, p, p]
     lib.cleave_execute_batched.restype = ctypes.c_int
+    lib.cleave_execute_assemble.argtypes = [p, p, i64, p, i64, ctypes.c_int, i64, i64,
+                                            p, i64, ctypes.c_int, i64, i64, i64, ctypes.c_int,
+                                            p, i64, i64, i64, ctypes.c_int, p]
+    lib.cleave_execute_assemble.restype = ctypes.c_int
     lib.cleave_reduce_batched.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p]
     lib.cleave_reduce_batched.restype = ctypes.c_int
     lib.cleave_reduce_residual.argtypes = [p, p, p, p, i64, ctypes.c_int, p]
@@ -283,6 +287,27 @@ def execute_batched(plan, A, a_strides, B, b_strides, n_inner, partials, transA=
         b_ptr, ldb, int(transB), int(b_strides[0]), int(b_strides[1]), int(n_inner),
         _dtype_code(A), ctypes.c_void_p(partials.data_ptr()), _stream_ptr(stream)),
         "cleave_execute_batched")
+
+
+def execute_assemble(plan, A, B, C, transA=0, transB=0, a_strides=(0, 0), b_strides=(0, 0),
+                     c_strides=(0, 0), n_inner=0, task_ids=None, stream=None):
+    """cleave_execute_assemble: plans without K-splits write their blocks
+    straight into C (fp32 or bf16).  For a batched plan A, B, C are the 2-D
+    tensors holding every member and the strides / n_inner say where."""
+    a_ptr, lda = _device_2d(A, "A")
+    b_ptr, ldb = _device_2d(B, "B")
+    c_ptr, ldc = _device_2d(C, "C")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    ids_ptr, n_ids = None, 0
+    if task_ids is not None:
+        ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+        ids_ptr, n_ids = ctypes.c_void_p(ids.ctypes.data), len(ids)
+    _check(_lib.cleave_execute_assemble(
+        plan._h, ids_ptr, n_ids, a_ptr, lda, int(transA), int(a_strides[0]), int(a_strides[1]),
+        b_ptr, ldb, int(transB), int(b_strides[0]), int(b_strides[1]), int(n_inner), _dtype_code(A),
+        c_ptr, ldc, int(c_strides[0]), int(c_strides[1]), _dtype_code(C), _stream_ptr(stream)),
+        "cleave_execute_assemble")
 
 
 def reduce_batched(plan, partials, C, c_strides, n_inner, stream=None):

@@ -124,7 +124,7 @@ const char* direct_kernel_name(int cls, int transA, int transB) {
 
 extern "C" int cleave_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" int cleave_version(void) { return 104; }
+extern "C" int cleave_version(void) { return 105; }
 
 extern "C" int cleave_plan_upload(cleave_plan* plan) {
   if (!plan) return CLEAVE_EINVAL;
@@ -144,18 +144,27 @@ namespace {
 struct BatchStrides {
   int64_t n_inner = 0;
   int64_t a_outer = 0, a_inner = 0, b_outer = 0, b_inner = 0;
+  int64_t c_outer = 0, c_inner = 0;   // assemble mode only
+};
+
+// Assemble mode: blocks go to their place in C instead of the partial buffer.
+struct AssembleTarget {
+  void* C = nullptr;
+  int64_t ldc = 0;
+  int out_dtype = CLEAVE_F32;
 };
 
 int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, const void* A,
                  int64_t lda, int transA, const void* B, int64_t ldb, int transB, int dtype,
-                 float* partials, const BatchStrides& bs, void* hip_stream) {
-  if (!plan || !A || !B || !partials) return CLEAVE_EINVAL;
+                 float* partials, const BatchStrides& bs, void* hip_stream,
+                 const AssembleTarget& asm_to = AssembleTarget{}) {
+  if (!plan || !A || !B || (!partials && !asm_to.C)) return CLEAVE_EINVAL;
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
   if ((task_ids == nullptr) != (n_ids == 0) || n_ids < 0) return CLEAVE_EINVAL;
   if (lda < (transA ? plan->M : plan->K) || ldb < (transB ? plan->K : plan->N)) return CLEAVE_EINVAL;
   const int eb = dtype == CLEAVE_BF16 ? 2 : 4;
-  if (!aligned(A, eb) || !aligned(B, eb) || !aligned(partials, 4)) return CLEAVE_EINVAL;
+  if (!aligned(A, eb) || !aligned(B, eb) || !aligned(partials, 4)) return CLEAVE_EINVAL;   // null partials: assemble mode
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
   // Work items of a subset, in the order the caller listed the tasks.
@@ -239,6 +248,11 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     args.a_inner = bs.a_inner;
     args.b_outer = bs.b_outer;
     args.b_inner = bs.b_inner;
+    args.C = asm_to.C;
+    args.ldc = asm_to.ldc;
+    args.c_bf16 = asm_to.out_dtype == CLEAVE_BF16 ? 1 : 0;
+    args.c_outer = bs.c_outer;
+    args.c_inner = bs.c_inner;
     const bool direct = vec && dtype == CLEAVE_BF16 &&
                         (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
     if (direct) {
@@ -295,6 +309,42 @@ extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids
   bs.b_inner = b_inner;
   return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials, bs,
                       hip_stream);
+}
+
+extern "C" int cleave_execute_assemble(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                                       const void* A, int64_t lda, int transA, int64_t a_outer,
+                                       int64_t a_inner, const void* B, int64_t ldb, int transB,
+                                       int64_t b_outer, int64_t b_inner, int64_t n_inner, int dtype,
+                                       void* C, int64_t ldc, int64_t c_outer, int64_t c_inner,
+                                       int out_dtype, void* hip_stream) {
+  if (!plan || !C) return CLEAVE_EINVAL;
+  if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  if (ldc < plan->N || !aligned(C, out_dtype == CLEAVE_BF16 ? 2 : 4)) return CLEAVE_EINVAL;
+  // a block is the finished output only if its task covers the whole inner dimension
+  for (const cleave_task& t : plan->tasks)
+    if (t.ksplit_cnt != 1) return CLEAVE_EINVAL;
+  BatchStrides bs;
+  if (plan->batch > 0) {
+    if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
+      return CLEAVE_EINVAL;
+    if (a_outer < 0 || a_inner < 0 || b_outer < 0 || b_inner < 0 || c_outer < 0 || c_inner < 0)
+      return CLEAVE_EINVAL;
+    bs.n_inner = n_inner;
+    bs.a_outer = a_outer;
+    bs.a_inner = a_inner;
+    bs.b_outer = b_outer;
+    bs.b_inner = b_inner;
+    bs.c_outer = c_outer;
+    bs.c_inner = c_inner;
+  } else if (n_inner != 0 || a_outer || a_inner || b_outer || b_inner || c_outer || c_inner) {
+    return CLEAVE_EINVAL;   // strides belong to batched plans
+  }
+  AssembleTarget to;
+  to.C = C;
+  to.ldc = ldc;
+  to.out_dtype = out_dtype;
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, nullptr, bs,
+                      hip_stream, to);
 }
 
 namespace {

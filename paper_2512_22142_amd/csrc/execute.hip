@@ -24,6 +24,7 @@
 
 #include "plan_internal.h"
 #include "kernels.h"
+#include "tile_store.h"
 
 namespace cleave {
 
@@ -340,42 +341,10 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
       }
     }
 
-    // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
-    // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
-    // half a wave writes one aligned 128-byte run per store.  One per-thread
-    // base pointer plus wave-uniform row offsets keeps the epilogue free of
-    // per-store address arithmetic.
-    const int64_t ldp = task.n_len;
     const int row0 = wm * WTM + lh * 4;
     const int col0 = wn * WTN + l32;
-    float* tp = args.partials + task.partial_off +
-                (static_cast<int64_t>(sub_m) * TM + row0) * ldp + sub_n * TN + col0;
-    if (m_valid == TM && n_valid == TN) {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ldp;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) p[j * 32] = acc[i][j][q * 4 + r];
-          }
-    } else {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int rr = i * 32 + q * 8 + r;
-            float* p = tp + static_cast<int64_t>(rr) * ldp;
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-              if (row0 + rr < m_valid && col0 + j * 32 < n_valid)
-                p[j * 32] = acc[i][j][q * 4 + r];
-          }
-    }
+    store_tile<MB, NB>(acc, tile_target(args, task, sub_m, sub_n, TM, TN), args.C && args.c_bf16, row0,
+                       col0, m_valid, n_valid, m_valid == TM && n_valid == TN);
   }
 }
 

@@ -37,6 +37,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "tile_store.h"
 #include "plan_internal.h"
 
 namespace cleave {
@@ -199,8 +200,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   struct ItemCtx {
     const unsigned char* a_ptr;   // first row of the A tile at the chunk's first k
     const unsigned char* b_ptr;
-    float* out;                   // element (0, 0) of this sub-tile in the partial block
-    int64_t ldp;                  // row stride of the partial block
+    TileTarget out;               // where this sub-tile's accumulators go
     int steps, m_valid, n_valid;
   };
   auto load_ctx = [&](int64_t it) -> ItemCtx {
@@ -221,8 +221,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     c.b_ptr = static_cast<const unsigned char*>(args.B) +
               (batch_offset(task.gemm_id, args.batch_inner, args.b_outer, args.b_inner) +
                n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
-    c.ldp = task.n_len;
-    c.out = args.partials + task.partial_off + static_cast<int64_t>(sub_m) * TM * c.ldp + sub_n * TN;
+    c.out = tile_target(args, task, sub_m, sub_n, TM, TN);
     return c;
   };
   const int64_t a_step = a_ks * S::BK * 2;    // bytes per K step
@@ -384,43 +383,11 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     // before this item's stores so that its latency hides behind them.
     const int row0 = wm * S::WTM + lh * 4;
     const int col0 = wn * S::WTN + l32;
-    const int64_t ldp = c.ldp;
-    float* tp = c.out + row0 * ldp + col0;
+    const TileTarget target = c.out;
     const int m_valid = c.m_valid, n_valid = c.n_valid;
     const bool interior = m_valid == TM && n_valid == TN;
     if (has_next) fill_ring(nx);
-
-    // Partial block: row-major m_len x n_len at partial_off.  A 32 x 32 MFMA
-    // block leaves lane l with column l % 32 and rows 8*q + 4*(l / 32) + r, so
-    // half a wave writes one aligned 128-byte run per store.  Plain stores:
-    // non-temporal ones make this kernel ~1 % faster but the reducer that
-    // follows ~10 % slower.
-    if (interior) {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ldp;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) p[j * 32] = acc[i][j][q * 4 + r];
-          }
-    } else {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int rr = i * 32 + q * 8 + r;
-            float* p = tp + static_cast<int64_t>(rr) * ldp;
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-              if (row0 + rr < m_valid && col0 + j * 32 < n_valid)
-                p[j * 32] = acc[i][j][q * 4 + r];
-          }
-    }
+    store_tile<MB, NB>(acc, target, args.C && args.c_bf16, row0, col0, m_valid, n_valid, interior);
     if (!has_next) break;
     static_assert(MB * NB * 16 >= 63, "a full epilogue must saturate the vector-memory counter");
     fill_landed = interior;

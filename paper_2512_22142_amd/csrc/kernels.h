@@ -22,6 +22,12 @@ struct ExecuteArgs {
   // the operands at element offsets o * outer + i * inner from A and B.
   uint32_t batch_inner;
   int64_t a_outer, a_inner, b_outer, b_inner;
+  // Assemble mode (C != nullptr): blocks go straight to their place in the
+  // output matrix (fp32, or bf16 when c_bf16 != 0) instead of `partials`.
+  void* C;
+  int64_t ldc;
+  int c_bf16;
+  int64_t c_outer, c_inner;
 };
 
 // Element offset of the operands of batch member `gemm_id` (0 for plain plans).
