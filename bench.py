@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "0a870d3017dc20ceb2e896c9b3ef50aefd4d865bb15a7fd787cdbf3b5e1f2220",
-    "execute_bytes_per_launch": (2.0 * 246943 + 396520) * 1024,
+    "sources_sha256": "a9b88c3c666558764ece6921ff78a0b45ebade1744bbabe79b6637fc7320a845",
+    "execute_bytes_per_launch": (2.0 * 243835 + 394338) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194456 + 97134) * 1024,
 }
 
