@@ -8,8 +8,43 @@
 All compute happens in libcleave.so (hand-written HIP for gfx950, C ABI in
 include/cleave.h); build it with `python -m paper_2512_22142_amd.build`.
 """
-from .binding import (  # noqa: F401
-    BF16, F32, CleaveError, Device, Plan, assign, shard_cost, shard_fits, TASK_DTYPE, EXPORTS, LIB_PATH,
-    execute, execute_assemble, execute_batched, plan_batched, plan_explicit, plan_uniform, reduce, reduce_adam, reduce_batched,
-    reduce_residual, verify, version,
+# The binding (and with it libcleave.so) is loaded on first use of any of these
+# names, so that `paper_2512_22142_amd.build` can be imported in a tree where
+# the library has not been built yet.  There is no fallback: if the library is
+# missing, the first use raises ImportError.
+_BINDING_NAMES = (
+    "BF16",
+    "F32",
+    "CleaveError",
+    "Device",
+    "Plan",
+    "assign",
+    "shard_cost",
+    "shard_fits",
+    "TASK_DTYPE",
+    "EXPORTS",
+    "LIB_PATH",
+    "execute",
+    "execute_assemble",
+    "execute_batched",
+    "plan_batched",
+    "plan_explicit",
+    "plan_uniform",
+    "reduce",
+    "reduce_adam",
+    "reduce_batched",
+    "reduce_residual",
+    "verify",
+    "version",
 )
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError("module %r has no attribute %r" % (__name__, name))
+
+
+def __dir__():
+    return sorted(list(globals()) + list(_BINDING_NAMES))
