@@ -203,7 +203,7 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
     // and column panels of B, at the same chunk of the inner dimension.
     order_work_items(p);
 
-    constexpr uint32_t kReduceElemsPerItem = 16384;
+    constexpr uint32_t kReduceElemsPerItem = 4096;
     for (uint32_t i = 0; i < p->tasks.size(); ++i) {
       const cleave_task& t = p->tasks[i];
       if (t.ksplit_idx != 0) continue;

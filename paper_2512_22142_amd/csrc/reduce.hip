@@ -6,7 +6,7 @@
 // instead feed one of the streaming operators the paper keeps on the PS
 // (residual add, Adam update) without being stored first: see the epilogues.
 //
-// One workgroup handles one reduce item (a run of rows of one tile, ~16K
+// One workgroup handles one reduce item (a run of rows of one tile, ~4K
 // elements).  The S blocks of a tile are adjacent in the partial buffer and
 // each block is contiguous, so every load of the vector path is a 16-byte
 // access into a contiguous stream.
