@@ -34,9 +34,9 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "a9b88c3c666558764ece6921ff78a0b45ebade1744bbabe79b6637fc7320a845",
-    "execute_bytes_per_launch": (2.0 * 243835 + 394338) * 1024,
-    "reduce_bytes_per_launch": (2.0 * 194456 + 97134) * 1024,
+    "sources_sha256": "14ffcb07358571a2d706ddb13c5d1d886e511ae95e6983cd8d0396f413cfc090",
+    "execute_bytes_per_launch": (2.0 * 244110 + 394338) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
 }
 
 
