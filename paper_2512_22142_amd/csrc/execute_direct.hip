@@ -316,6 +316,22 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
               acc[i][j], 0, 0, 0);
     };
 
+    // Instruction order of one sub-step, as a hint to the scheduler: the MFMAs
+    // of the current fragments with the LDS reads of the next fragments spread
+    // one (or two, for transpose reads) behind each of them, the last two
+    // MFMAs without reads.  Measured +2 % over the compiler's own order.
+    auto interleave = [&]() {
+      constexpr int kReads = (A_K ? MB : 2 * MB) + (B_K ? NB : 2 * NB);
+      constexpr int kMfma = MB * NB;
+      constexpr int kTail = kMfma > 2 ? 2 : kMfma - 1;             // MFMAs without reads behind them
+      constexpr int kPer = (kReads + (kMfma - kTail) - 1) / (kMfma - kTail);
+#pragma unroll
+      for (int i = 0; i < kMfma; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one MFMA
+        if (i < kMfma - kTail) __builtin_amdgcn_sched_group_barrier(0x100, kPer, 0);   // LDS reads
+      }
+    };
+
     // Step 0 must have landed.  All earlier fragment reads of this workgroup
     // completed before the previous item's final barrier.
     if (fill_landed) {
@@ -340,6 +356,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         constexpr int J = decltype(j_tag)::value;
         read_frags(st, int_c<J + 1>{}, (J + 1) & 1);
         mma(J & 1);
+        interleave();
       };
       sub(int_c<0>{});
       if constexpr (kSub == 4) {
@@ -358,6 +375,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       if (s + STAGES < steps) issue(c, s + STAGES, ST);
       if (s + 1 < steps) read_frags(int_c<(ST + 1) % STAGES>{}, int_c<0>{}, 0);
       mma((kSub - 1) & 1);
+      interleave();
     };
     int s = 0;
     for (; s + STAGES <= steps; s += STAGES) {
