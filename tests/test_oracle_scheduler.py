@@ -133,3 +133,43 @@ def test_memory_limits_shape_the_layout_or_make_it_infeasible():
         sc.assign(256, 256, n, b, small[:15], 64)        # 15 such devices cannot cover 16 shards
     with pytest.raises(ValueError):
         sc.assign(0, 8, 8, 2, small, 8)
+
+
+def area_lower_bound(m, q, n, b, devs, upper):
+    """Smallest T at which the devices' largest affordable shard areas (any
+    shape, searched on a geometric grid of heights) add up to the output: no
+    assignment, guillotine or not, can finish sooner."""
+    def max_area(d, T):
+        best, x = 0, 1.0
+        heights = {m}
+        while x <= m:
+            heights.add(int(x))
+            x *= 1.15
+        for al in heights:
+            lo, hi = 0, q
+            while lo < hi:
+                mid = (lo + hi + 1) // 2
+                if sc.shard_cost(d, al, mid, n, b) <= T and sc.shard_fits(d, al, mid, n, b):
+                    lo = mid
+                else:
+                    hi = mid - 1
+            best = max(best, al * lo)
+        return best
+    lo, hi = 0.0, upper
+    for _ in range(40):
+        mid = (lo + hi) / 2
+        if sum(max_area(d, mid) for d in devs) >= m * q:
+            hi = mid
+        else:
+            lo = mid
+    return lo          # infeasible side: a true lower bound up to the height grid
+
+
+@pytest.mark.parametrize("m,q,n,k,g", [(4096, 4096, 4096, 32, 64), (4096, 11008, 4096, 100, 64), (1000, 777, 333, 7, 16)])
+def test_heuristic_stays_close_to_the_area_lower_bound_on_seeded_fleets(m, q, n, k, g):
+    from workloads import draw_fleet
+    devs = [sc.Device(*d) for d in draw_fleet(k, 100 + k)]
+    res = sc.assign(m, q, n, 2, devs, g)
+    check_layout(m, q, n, 2, devs, g, res)
+    lb = area_lower_bound(m, q, n, 2, devs, res[3])
+    assert lb <= res[3] <= 1.35 * lb, (res[3], lb)
