@@ -50,6 +50,8 @@ void free_device_tables(cleave_plan* p) {
   if (p->d_reduce_items) (void)hipFree(p->d_reduce_items);
   if (p->d_subset_items) (void)hipFree(p->d_subset_items);
   p->d_tasks = nullptr;
+  if (p->d_items_fine) (void)hipFree(p->d_items_fine);
+  p->d_items_fine = nullptr;
   p->d_items[0] = p->d_items[1] = nullptr;
   p->d_reduce_items = nullptr;
   p->d_subset_items = nullptr;
@@ -76,6 +78,7 @@ int ensure_uploaded(cleave_plan* p) {
   int rc = upload_vector(p->tasks, &p->d_tasks);
   for (int c = 0; rc == CLEAVE_OK && c < cleave::kNumTileClasses; ++c)
     rc = upload_vector(p->items[c], &p->d_items[c]);
+  if (rc == CLEAVE_OK) rc = upload_vector(p->items_fine, &p->d_items_fine);
   if (rc == CLEAVE_OK) rc = upload_vector(p->reduce_items, &p->d_reduce_items);
   if (rc != CLEAVE_OK) {
     free_device_tables(p);
@@ -167,6 +170,17 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   if (!aligned(A, eb) || !aligned(B, eb) || !aligned(partials, 4)) return CLEAVE_EINVAL;   // null partials: assemble mode
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+  int cus = 0;
+  int rc = compute_units(&cus);
+  if (rc != CLEAVE_OK) return rc;
+  // The large class runs one workgroup per CU; when its items would leave
+  // half of the CUs or more idle, every block is cut into small sub-tiles
+  // instead (four times as many items, two workgroups per CU).  The bits do
+  // not depend on the cut.
+  const auto prefers_fine = [cus](size_t large_items) {
+    return large_items > 0 && large_items <= static_cast<size_t>(cus) / 2;
+  };
+
   // Work items of a subset, in the order the caller listed the tasks.
   std::vector<cleave::WorkItem> subset[cleave::kNumTileClasses];
   if (task_ids) {
@@ -178,12 +192,18 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
         seen[id] = true;
         cleave::append_work_items(plan->tasks[id], static_cast<uint32_t>(id), subset);
       }
+      if (prefers_fine(subset[cleave::kTileLarge].size())) {
+        subset[0].clear();
+        subset[1].clear();
+        for (int64_t i = 0; i < n_ids; ++i)
+          cleave::append_work_items(plan->tasks[task_ids[i]], static_cast<uint32_t>(task_ids[i]), subset, true);
+      }
     } catch (const std::bad_alloc&) {
       return CLEAVE_ENOMEM;
     }
   }
 
-  int rc = ensure_uploaded(plan);
+  rc = ensure_uploaded(plan);
   if (rc != CLEAVE_OK) return rc;
 
   // 16-byte load path: every chunk and tile edge a multiple of 16 bytes and
@@ -200,6 +220,12 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   const cleave::WorkItem* d_lists[cleave::kNumTileClasses] = {plan->d_items[0], plan->d_items[1]};
   int64_t counts[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items[0].size()),
                                              static_cast<int64_t>(plan->items[1].size())};
+  if (!task_ids && prefers_fine(plan->items[cleave::kTileLarge].size())) {
+    d_lists[cleave::kTileLarge] = nullptr;
+    counts[cleave::kTileLarge] = 0;
+    d_lists[cleave::kTileSmall] = plan->d_items_fine;
+    counts[cleave::kTileSmall] = static_cast<int64_t>(plan->items_fine.size());
+  }
   if (task_ids) {
     // The subset tables live in a scratch buffer of the plan that a previous
     // subset launch on this stream may still be reading: wait, refill, and
@@ -259,9 +285,6 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
       // Persistent workgroups, as many as the chip holds at once: each walks
       // the item list with the grid as stride and fetches the head of its next
       // item while it stores the current one.
-      int cus = 0;
-      rc = compute_units(&cus);
-      if (rc != CLEAVE_OK) return rc;
       const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(c);
       const int grid = static_cast<int>(std::min<int64_t>(counts[c], resident));
       CLEAVE_HIP(cleave::launch_execute_direct(args, c, grid, stream));

@@ -51,9 +51,16 @@ void order_work_items(cleave_plan* p) {
       gn = kXcds / g;
     }
   }
-  std::vector<WorkItem> all[kNumTileClasses];
-  for (uint32_t i = 0; i < p->tasks.size(); ++i) append_work_items(p->tasks[i], i, all);
-  for (int cls = 0; cls < kNumTileClasses; ++cls) {
+  // three lists: the two classes of the mixed cut, then the all-small cut
+  std::vector<WorkItem> all[kNumTileClasses], fine[kNumTileClasses];
+  for (uint32_t i = 0; i < p->tasks.size(); ++i) {
+    append_work_items(p->tasks[i], i, all);
+    append_work_items(p->tasks[i], i, fine, true);
+  }
+  for (int list = 0; list < kNumTileClasses + 1; ++list) {
+    const int cls = list < kNumTileClasses ? list : kTileSmall;
+    const std::vector<WorkItem>& source = list < kNumTileClasses ? all[cls] : fine[kTileSmall];
+    std::vector<WorkItem>& ordered = list < kNumTileClasses ? p->items[cls] : p->items_fine;
     const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
     const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
     struct Key {
@@ -61,7 +68,7 @@ void order_work_items(cleave_plan* p) {
       WorkItem item;
     };
     std::vector<Key> lists[kXcds];
-    for (const WorkItem& w : all[cls]) {
+    for (const WorkItem& w : source) {
       const cleave_task& t = p->tasks[w.task];
       const uint32_t sub_cols = (t.n_len + tc - 1) / tc;
       const uint32_t m = t.m0 + (w.sub / sub_cols) * tr;
@@ -91,7 +98,7 @@ void order_work_items(cleave_plan* p) {
     // Interleave; when a region runs out, the slot is filled from the region
     // that has most left, so the list has no holes.
     size_t pos[kXcds] = {};
-    p->items[cls].reserve(all[cls].size());
+    ordered.reserve(source.size());
     for (size_t i = 0; i < longest; ++i) {
       for (int x = 0; x < kXcds; ++x) {
         int src = x;
@@ -107,11 +114,11 @@ void order_work_items(cleave_plan* p) {
           }
           if (src < 0) break;
         }
-        p->items[cls].push_back(lists[src][pos[src]++].item);
+        ordered.push_back(lists[src][pos[src]++].item);
       }
     }
     for (int x = 0; x < kXcds; ++x)
-      for (; pos[x] < lists[x].size(); ++pos[x]) p->items[cls].push_back(lists[x][pos[x]].item);
+      for (; pos[x] < lists[x].size(); ++pos[x]) ordered.push_back(lists[x][pos[x]].item);
   }
 }
 
@@ -222,8 +229,9 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
 
 }  // namespace
 
-void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out) {
-  const int cls = tile_class_of(t);
+void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out,
+                       bool fine) {
+  const int cls = fine ? static_cast<int>(kTileSmall) : tile_class_of(t);
   const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
   const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
   const uint64_t sm = (t.m_len + tr - 1) / tr;

@@ -84,8 +84,12 @@ struct VerifyTables {
   double* d_item_sums = nullptr;  // one per item
 };
 
-// Appends the work items of `task_index` (record t) to out[class].
-void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out);
+// Appends the work items of `task_index` (record t) to out[class].  With
+// `fine` every block is cut into small-class sub-tiles.  Either cut gives the
+// same bits: both kernels shapes accumulate an output element in the same
+// order (ascending K steps and sub-steps), so the choice is free per launch.
+void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out,
+                       bool fine = false);
 
 }  // namespace cleave
 
@@ -103,12 +107,16 @@ struct cleave_plan {
   bool all_n_mult4 = true;   // every n0, n_len multiple of 4 (vector path of reduce)
   std::vector<cleave_task> tasks;
   std::vector<cleave::WorkItem> items[cleave::kNumTileClasses];  // all tasks, launch order
+  // All tasks cut into small-class sub-tiles only: used when the large class
+  // would leave most of the CUs without a work item.
+  std::vector<cleave::WorkItem> items_fine;
   std::vector<cleave::ReduceItem> reduce_items;
 
   // Device copies (current device at first use).
   int device = -1;
   cleave_task* d_tasks = nullptr;
   cleave::WorkItem* d_items[cleave::kNumTileClasses] = {nullptr, nullptr};
+  cleave::WorkItem* d_items_fine = nullptr;
   cleave::ReduceItem* d_reduce_items = nullptr;
   // Scratch for subset launches; grown on demand, reused by later calls.
   cleave::WorkItem* d_subset_items = nullptr;
