@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "88f58c4f4698000c489bb2171053bbe1409bbdc2ba407cab79c43f70375f97b7",
-    "execute_bytes_per_launch": (2.0 * 243678 + 395020) * 1024,
+    "sources_sha256": "172b0a244d26cafe3ec03ef2a1e753d5c5487fc927c22e156db8be70d12d6a74",
+    "execute_bytes_per_launch": (2.0 * 244986 + 395020) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
 }
 
