@@ -214,7 +214,9 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
     for (uint32_t i = 0; i < p->tasks.size(); ++i) {
       const cleave_task& t = p->tasks[i];
       if (t.ksplit_idx != 0) continue;
-      const uint32_t rows_per = std::max<uint32_t>(1, kReduceElemsPerItem / t.n_len);
+      // a single split is a plain copy: fewer, longer items do better there
+      const uint32_t elems = t.ksplit_cnt == 1 ? 4 * kReduceElemsPerItem : kReduceElemsPerItem;
+      const uint32_t rows_per = std::max<uint32_t>(1, elems / t.n_len);
       for (uint32_t r = 0; r < t.m_len; r += rows_per) {
         p->reduce_items.push_back(ReduceItem{i, r, std::min(rows_per, t.m_len - r), 0});
       }
