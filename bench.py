@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "172b0a244d26cafe3ec03ef2a1e753d5c5487fc927c22e156db8be70d12d6a74",
-    "execute_bytes_per_launch": (2.0 * 244986 + 395020) * 1024,
+    "sources_sha256": "dec5144d541612d494d44f9ce9a606cb1c2e70c2fa94fd4837189d8388203f05",
+    "execute_bytes_per_launch": (2.0 * 243730 + 395020) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
 }
 
