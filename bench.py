@@ -34,7 +34,7 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "dec5144d541612d494d44f9ce9a606cb1c2e70c2fa94fd4837189d8388203f05",
+    "sources_sha256": "86a2ed9f7266b6c260456f0ffc0615dd70c02ac5ccd33254fb48dc617789c117",
     "execute_bytes_per_launch": (2.0 * 243730 + 395020) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
 }

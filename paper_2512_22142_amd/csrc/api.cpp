@@ -390,9 +390,6 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
 
   int rc = ensure_uploaded(plan);
   if (rc != CLEAVE_OK) return rc;
-  int cus = 0;
-  rc = compute_units(&cus);
-  if (rc != CLEAVE_OK) return rc;
 
   bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
              c_outer % 4 == 0 && c_inner % 4 == 0;
@@ -410,7 +407,8 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   args.batch_inner = static_cast<uint32_t>(n_inner);
   args.c_outer = c_outer;
   args.c_inner = c_inner;
-  const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20)); (void)cus;
+  // one workgroup per reduce item (the kernel loops only if the grid is capped)
+  const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20));
   if (epi.adam) {
     CLEAVE_HIP(cleave::launch_reduce_adam(args, *epi.adam, vec, grid, stream));
   } else if (epi.residual) {

@@ -2,9 +2,11 @@
 // rows of A with its columns of B; here restricted to its chunk of the inner
 // dimension, and the fp32 partial block goes to the task's slot in HBM).
 //
-// One workgroup (4 wave64, 2 x 2) computes one work item: a 256 x 128 (or
-// 128 x 128) sub-tile of a task's output block over the task's whole chunk
-// [k0, k0 + k_len).  A wave owns a 128 x 64 (64 x 64) patch.  The inner loop
+// This is the staged executor: fp32 inputs, chunk lengths or tile edges the
+// bf16 direct-to-LDS path does not take, unaligned operands.  One workgroup
+// computes one work item: a 256 x 256 sub-tile (8 wave64 as 2 x 4, a wave owns
+// 128 x 64) or a 128 x 128 one (4 waves as 2 x 2, 64 x 64 each) of a task's
+// output block over the task's whole chunk [k0, k0 + k_len).  The inner loop
 // walks the chunk in ascending steps of 128 bytes of K per row (64 bf16 / 32
 // fp32 elements) and, inside a step, in ascending 32-byte sub-steps; the order
 // of the MFMA accumulation for an output element therefore depends only on
@@ -15,9 +17,9 @@
 // fragment reads are bank-conflict free; operands whose storage is not
 // K-contiguous are transposed in registers on the way) -> 16-byte fragment
 // reads -> MFMA 32x32x16 bf16 (or 32x32x2 fp32) into fp32 accumulators ->
-// stores of the partial block.  Registers and LDS are sized so that two
+// stores of the partial block.  The small class is sized so that two
 // workgroups share a CU: while one waits at a barrier, refills LDS or drains
-// its partial-block stores, the other keeps the matrix cores busy.
+// its stores, the other keeps the matrix cores busy.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
