@@ -94,3 +94,32 @@ def test_work_on_a_side_stream():
     dA, dB = A.cuda(), B.cuda()
     torch.cuda.synchronize()
     run_and_check(A, B, 0, 0, (M, N, K, 256, 256, 2), "bf16", dA=dA, dB=dB, stream=side)
+
+
+def test_execute_and_reduce_replay_from_a_hip_graph():
+    """The full-plan calls allocate nothing and record no memset nodes: captured
+    once, every replay reproduces the eager result bit for bit."""
+    M, N, K = 1024, 768, 512
+    A = make_matrix(211, M, K, "bf16").cuda()
+    B = make_matrix(212, K, N, "bf16", std=0.02).cuda()
+    plan = cleave.plan_uniform(M, N, K, 256, 256, 2)
+    parts = torch.empty(plan.partial_elems, dtype=torch.float32, device="cuda")
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    cleave.execute(plan, A, B, parts)          # eager: also uploads tables and sets kernel attributes
+    cleave.reduce(plan, parts, C)
+    torch.cuda.synchronize()
+    eager = C.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cleave.execute(plan, A, B, parts)
+        cleave.reduce(plan, parts, C)
+    for replay in range(3):
+        parts.fill_(float("nan"))
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C.view(torch.int32), eager.view(torch.int32)), replay
+        # eager work of the program between replays
+        cleave.execute(plan, A, B, parts)
+        torch.cuda.synchronize()
