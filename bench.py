@@ -119,17 +119,22 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step(events=None):
+        # one event between consecutive launches: the end of one kernel's
+        # interval is the start of the next one's
+        if events is not None:
+            prev = torch.cuda.Event(enable_timing=True)
+            prev.record(stream)
         for i, (g, plan, dA, dB) in enumerate(gemms):
-            if events is not None:
-                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-                e0.record(stream)
             cleave.execute(plan, dA, dB, slots[i], g.transA, g.transB)
             if events is not None:
-                e1.record(stream)
+                mid = torch.cuda.Event(enable_timing=True)
+                mid.record(stream)
             cleave.reduce(plan, slots[i], outputs[i])
             if events is not None:
-                e2.record(stream)
-                events.append((i, e0, e1, e2))
+                end = torch.cuda.Event(enable_timing=True)
+                end.record(stream)
+                events.append((i, prev, mid, end))
+                prev = end
 
     for _ in range(args.warmup):
         step()
