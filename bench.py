@@ -73,6 +73,8 @@ def main():
     import numpy as np
     import torch
 
+    from paper_2512_22142_amd.build import ensure_built
+    ensure_built()                      # uses the built library; builds only if there is none
     import paper_2512_22142_amd as cleave
     from workloads import layer_config, make_gemm_operands
 

@@ -51,5 +51,13 @@ def build(verbose=True, extra=None):
     return LIB
 
 
+def ensure_built(verbose=False):
+    """Builds the library only if none is there (tests, the smoke check and the
+    benchmark use what is built; after a change to a source, build again)."""
+    if not os.path.exists(LIB):
+        build(verbose=verbose)
+    return LIB
+
+
 if __name__ == "__main__":
     print(build(extra=sys.argv[1:]))

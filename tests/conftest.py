@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The tests use the library that is built; they build it only if none is there.
+    from paper_2512_22142_amd.build import ensure_built
+    ensure_built()
 
 
 def read_golden(name):
