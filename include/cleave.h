@@ -292,6 +292,20 @@ int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
                   int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
                   int32_t* tile_device, double* cost);
 
+/* Churn re-solve (paper Sec. 4.2): the m x q rectangle is the unfinished output
+ * of failed devices, starting at (row0, col0) of the GEMM's output; devs are
+ * the survivors.  cached[4k .. 4k+3] = [row_lo, row_hi, col_lo, col_hi): the
+ * rows of A and columns of B survivor k already holds (absolute indices; an
+ * empty interval if none), which it does not download again; mem_used[k] =
+ * bytes of its memory already taken (no cache replacement during a GEMM).
+ * Same construction, outputs and errors as cleave_assign, with the cache-aware
+ * downlink term; also CLEAVE_EINVAL for NULL / negative / inverted intervals. */
+int cleave_reassign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                    const cleave_device* devs, int32_t n_devs, int64_t granule,
+                    int64_t row0, int64_t col0, const int64_t* cached, const double* mem_used,
+                    int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
+                    int32_t* tile_device, double* cost);
+
 /* ---- misc ----------------------------------------------------------------*/
 const char* cleave_strerror(int status);
 /* hipError_t value of the most recent CLEAVE_EHIP on this thread (0 if none). */

@@ -20,7 +20,9 @@ takes a deterministic heuristic instead (stated here in full, because the
 library's planner is tested for producing the same layout):
 
   feasible(T): each device's edge e_k = largest multiple of the granule g (at
-  most max(m, q) rounded up) with C(e_k, e_k) <= T and the memory constraint;
+  most max(m, q) rounded up) with C(e_k, e_k) <= T and the memory constraint
+  (in a churn re-solve, with the rows and columns of the rectangle that the
+  device already holds counted as not to be fetched);
   devices are ordered by e_k descending (index ascending on ties), devices
   with e_k = 0 stay idle.  Row bands are cut top to bottom: a band takes the
   next unused device, its height is h = min(e_k, rows left); inside the band
@@ -82,13 +84,53 @@ def _largest(limit_units, g, ok):
     return lo
 
 
-def _layout(m, q, n, b, devs, g, T):
-    """The construction for target time T; returns None if the devices run out."""
+def _overlap(lo, hi, c_lo, c_hi):
+    return max(0, min(hi, c_hi) - max(lo, c_lo))
+
+
+def _layout(m, q, n, b, devs, g, T, origin=(0, 0), cached=None, mem_used=None):
+    """The construction for target time T; returns None if the devices run out.
+
+    Churn recovery (Sec. 4.2): `cached[k]` = (row_lo, row_hi, col_lo, col_hi), the
+    rows of A and columns of B device k already holds (absolute indices; the
+    rectangle to cover starts at `origin`), which it need not download again;
+    `mem_used[k]` = bytes of its memory already taken (no cache replacement)."""
     top = -(-max(m, q) // g)
+
+    def cost_at(k, r_lo, h, c_lo, w):
+        d = devs[k]
+        if cached is None:
+            return shard_cost(d, h, w, n, b)
+        rl, rh, cl, ch = cached[k]
+        a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
+        return shard_cost(d, h, w, n, b, h - _overlap(a_lo, a_lo + h, rl, rh), w - _overlap(c0, c0 + w, cl, ch))
+
+    def fits_at(k, r_lo, h, c_lo, w):
+        d = devs[k]
+        if cached is None:
+            return shard_fits(d, h, w, n, b)
+        rl, rh, cl, ch = cached[k]
+        a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
+        af = h - _overlap(a_lo, a_lo + h, rl, rh)
+        bf = w - _overlap(c0, c0 + w, cl, ch)
+        return float(af * n * b + n * bf * b + h * w * b) + mem_used[k] <= d.mem_bytes
+
     edges = []
     for k, d in enumerate(devs):
-        e = _largest(top, g, lambda x: shard_cost(d, x, x, n, b) <= T and shard_fits(d, x, x, n, b)) * g
-        edges.append(e)
+        # the shard's position is not known yet: the edge counts every cached row
+        # and column of the rectangle as if the shard were placed on them
+        used = 0.0 if mem_used is None else mem_used[k]
+        if cached is None:
+            hr = hc = 0
+        else:
+            hr = _overlap(origin[0], origin[0] + m, cached[k][0], cached[k][1])
+            hc = _overlap(origin[1], origin[1] + q, cached[k][2], cached[k][3])
+
+        def ok(x, d=d, hr=hr, hc=hc, used=used):
+            af, bf = max(0, x - hr), max(0, x - hc)
+            return (shard_cost(d, x, x, n, b, af, bf) <= T and
+                    float(af * n * b + n * bf * b + x * x * b) + used <= d.mem_bytes)
+        edges.append(_largest(top, g, ok) * g)
     order = sorted((k for k in range(len(devs)) if edges[k] > 0), key=lambda k: (-edges[k], k))
     band_h, col_w, owner = [], [], []
     pos = 0
@@ -104,11 +146,11 @@ def _layout(m, q, n, b, devs, g, T):
                 return None
             k = order[pos]
             pos += 1
-            d = devs[k]
+            r_lo, c_lo = m - rows_left, q - cols_left
 
-            def ok(w, d=d, h=h, cols_left=cols_left):
+            def ok(w, k=k, h=h, cols_left=cols_left, r_lo=r_lo, c_lo=c_lo):
                 w = min(w, cols_left)
-                return shard_cost(d, h, w, n, b) <= T and shard_fits(d, h, w, n, b)
+                return cost_at(k, r_lo, h, c_lo, w) <= T and fits_at(k, r_lo, h, c_lo, w)
             w = min(_largest(-(-cols_left // g), g, ok) * g, cols_left)
             if w == 0:
                 continue
@@ -122,17 +164,22 @@ def _layout(m, q, n, b, devs, g, T):
     return band_h, col_w, owner
 
 
-def assign(m, q, n, b, devs, granule):
+def assign(m, q, n, b, devs, granule, origin=(0, 0), cached=None, mem_used=None):
     """Returns (band_h, col_w, owner, cost): band heights (sum m), one list of
     column widths per band (each sums to q), the device of every tile, and the
     GEMM cost max_k C(alpha_k, beta_k).  Raises ValueError if no feasible
-    layout exists (memory)."""
+    layout exists (memory).  With `cached` / `mem_used` / `origin` this is the
+    churn re-solve of Sec. 4.2: the m x q rectangle is the failed devices'
+    unfinished output, `devs` the survivors, and the downlink term counts only
+    rows and columns a device does not hold yet."""
     if min(m, q, n, b, granule) < 1 or not devs:
         raise ValueError("sizes must be positive and the device list non-empty")
+    if (cached is None) != (mem_used is None):
+        raise ValueError("cached and mem_used come together")
     t_hi = 1e-9
     found = None
     for _ in range(80):
-        found = _layout(m, q, n, b, devs, granule, t_hi)
+        found = _layout(m, q, n, b, devs, granule, t_hi, origin, cached, mem_used)
         if found is not None:
             break
         t_hi *= 2.0
@@ -141,16 +188,27 @@ def assign(m, q, n, b, devs, granule):
     lo, hi = 0.0, t_hi
     for _ in range(64):
         mid = (lo + hi) / 2.0
-        lay = _layout(m, q, n, b, devs, granule, mid)
+        lay = _layout(m, q, n, b, devs, granule, mid, origin, cached, mem_used)
         if lay is not None:
             hi, found = mid, lay
         else:
             lo = mid
     band_h, col_w, owner = found
     cost = 0.0
+    r_lo = 0
     for h, widths, owners in zip(band_h, col_w, owner):
+        c_lo = 0
         for w, k in zip(widths, owners):
-            cost = max(cost, shard_cost(devs[k], h, w, n, b))
+            if cached is None:
+                c = shard_cost(devs[k], h, w, n, b)
+            else:
+                rl, rh, cl, ch = cached[k]
+                a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
+                c = shard_cost(devs[k], h, w, n, b, h - _overlap(a_lo, a_lo + h, rl, rh),
+                               w - _overlap(c0, c0 + w, cl, ch))
+            cost = max(cost, c)
+            c_lo += w
+        r_lo += h
     return band_h, col_w, owner, cost
 
 

@@ -36,7 +36,7 @@ EXPORTS = (
     "cleave_reduce", "cleave_strerror", "cleave_last_hip_error", "cleave_version",
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
-    "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_execute_assemble",
+    "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
 )
 
 
@@ -109,6 +109,8 @@ def _load():
     lib.cleave_shard_fits.restype = ctypes.c_int
     lib.cleave_assign.argtypes = [i64, i64, i64, i32, p, i32, i64, p, p, p, p, p, p]
     lib.cleave_assign.restype = ctypes.c_int
+    lib.cleave_reassign.argtypes = [i64, i64, i64, i32, p, i32, i64, i64, i64, p, p, p, p, p, p, p, p]
+    lib.cleave_reassign.restype = ctypes.c_int
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
@@ -401,9 +403,11 @@ def shard_fits(dev, alpha, beta, n, elem_bytes):
     return bool(rc)
 
 
-def assign(m, q, n, elem_bytes, devices, granule):
+def assign(m, q, n, elem_bytes, devices, granule, origin=(0, 0), cached=None, mem_used=None):
     """cleave_assign (host only): returns (band_h, col_w, owner, cost) with one
-    list of column widths and of owning device indices per band."""
+    list of column widths and of owning device indices per band.  With `cached`
+    (one (row_lo, row_hi, col_lo, col_hi) per device) and `mem_used`:
+    cleave_reassign, the churn re-solve."""
     k = len(devices)
     devs = (Device * max(k, 1))(*devices)
     n_bands = ctypes.c_int32()
@@ -412,8 +416,17 @@ def assign(m, q, n, elem_bytes, devices, granule):
     col_w = (ctypes.c_int64 * max(k, 1))()
     owner = (ctypes.c_int32 * max(k, 1))()
     cost = ctypes.c_double()
-    _check(_lib.cleave_assign(m, q, n, elem_bytes, devs, k, granule, ctypes.byref(n_bands), band_h,
-                              n_cols, col_w, owner, ctypes.byref(cost)), "cleave_assign")
+    if cached is None:
+        _check(_lib.cleave_assign(m, q, n, elem_bytes, devs, k, granule, ctypes.byref(n_bands), band_h,
+                                  n_cols, col_w, owner, ctypes.byref(cost)), "cleave_assign")
+    else:
+        if mem_used is None or len(cached) != k or len(mem_used) != k:
+            raise CleaveError(EINVAL, "assign (cached / mem_used lengths)")
+        flat = (ctypes.c_int64 * (4 * max(k, 1)))(*[int(x) for c in cached for x in c])
+        used = (ctypes.c_double * max(k, 1))(*[float(x) for x in mem_used])
+        _check(_lib.cleave_reassign(m, q, n, elem_bytes, devs, k, granule, int(origin[0]), int(origin[1]),
+                                    flat, used, ctypes.byref(n_bands), band_h, n_cols, col_w, owner,
+                                    ctypes.byref(cost)), "cleave_reassign")
     bands, widths, owners, pos = [], [], [], 0
     for bnd in range(n_bands.value):
         c = n_cols[bnd]

@@ -127,7 +127,7 @@ const char* direct_kernel_name(int cls, int transA, int transB) {
 
 extern "C" int cleave_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" int cleave_version(void) { return 105; }
+extern "C" int cleave_version(void) { return 106; }
 
 extern "C" int cleave_plan_upload(cleave_plan* plan) {
   if (!plan) return CLEAVE_EINVAL;

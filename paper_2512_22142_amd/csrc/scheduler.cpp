@@ -59,15 +59,55 @@ int64_t largest(int64_t limit, F ok) {
   return lo;
 }
 
+// What the survivors of a device failure already hold (churn recovery,
+// Sec. 4.2): per device its cached rows of A [row_lo, row_hi) and columns of B
+// [col_lo, col_hi) in absolute output coordinates, the bytes of its memory
+// already in use (no cache replacement), and where the rectangle to cover
+// starts.  Null `cached`: cold start.
+struct Caches {
+  const int64_t* cached = nullptr;   // 4 per device
+  const double* mem_used = nullptr;  // 1 per device
+  int64_t row0 = 0, col0 = 0;
+};
+
+int64_t overlap(int64_t lo, int64_t hi, int64_t c_lo, int64_t c_hi) {
+  return std::max<int64_t>(0, std::min(hi, c_hi) - std::max(lo, c_lo));
+}
+
 bool build_layout(int64_t m, int64_t q, int64_t n, int64_t b, const cleave_device* devs,
-                  int32_t n_devs, int64_t g, double T, Layout* out) {
+                  int32_t n_devs, int64_t g, double T, const Caches& cc, Layout* out) {
   const int64_t top = (std::max(m, q) + g - 1) / g;
+  // rows / columns of a shard at (r_lo, c_lo) of the rectangle that device k must still fetch
+  auto fetch = [&](int32_t k, int64_t r_lo, int64_t h, int64_t c_lo, int64_t w, int64_t* af, int64_t* bf) {
+    if (!cc.cached) {
+      *af = h;
+      *bf = w;
+      return;
+    }
+    const int64_t* c = cc.cached + 4 * static_cast<int64_t>(k);
+    const int64_t a_lo = cc.row0 + r_lo, b_lo = cc.col0 + c_lo;
+    *af = h - overlap(a_lo, a_lo + h, c[0], c[1]);
+    *bf = w - overlap(b_lo, b_lo + w, c[2], c[3]);
+  };
+  auto affordable = [&](int32_t k, int64_t h, int64_t w, int64_t af, int64_t bf) {
+    const cleave_device& d = devs[k];
+    if (cost_of(d, h, w, af, bf, n, b) > T) return false;
+    if (!cc.cached) return fits(d, h, w, n, b);
+    return static_cast<double>(af * n * b + n * bf * b + h * w * b) + cc.mem_used[k] <= d.mem_bytes;
+  };
   std::vector<int64_t> edge(n_devs);
   for (int32_t k = 0; k < n_devs; ++k) {
-    const cleave_device& d = devs[k];
+    // the shard's position is not known yet: every cached row and column of the
+    // rectangle counts as if the shard were placed on it
+    int64_t hr = 0, hc = 0;
+    if (cc.cached) {
+      const int64_t* c = cc.cached + 4 * static_cast<int64_t>(k);
+      hr = overlap(cc.row0, cc.row0 + m, c[0], c[1]);
+      hc = overlap(cc.col0, cc.col0 + q, c[2], c[3]);
+    }
     edge[k] = g * largest(top, [&](int64_t u) {
                 const int64_t e = u * g;
-                return cost_of(d, e, e, e, e, n, b) <= T && fits(d, e, e, n, b);
+                return affordable(k, e, e, std::max<int64_t>(0, e - hr), std::max<int64_t>(0, e - hc));
               });
   }
   std::vector<int32_t> order;
@@ -89,10 +129,12 @@ bool build_layout(int64_t m, int64_t q, int64_t n, int64_t b, const cleave_devic
     while (cols_left > 0) {
       if (pos >= order.size()) return false;
       const int32_t k = order[pos++];
-      const cleave_device& d = devs[k];
+      const int64_t r_lo = m - rows_left, c_lo = q - cols_left;
       const int64_t units = largest((cols_left + g - 1) / g, [&](int64_t u) {
         const int64_t w = std::min(u * g, cols_left);
-        return cost_of(d, h, w, h, w, n, b) <= T && fits(d, h, w, n, b);
+        int64_t af, bf;
+        fetch(k, r_lo, h, c_lo, w, &af, &bf);
+        return affordable(k, h, w, af, bf);
       });
       const int64_t w = std::min(units * g, cols_left);
       if (w == 0) continue;   // this device stays idle
@@ -139,10 +181,11 @@ extern "C" int cleave_shard_fits(const cleave_device* dev, int64_t alpha, int64_
   return fits(*dev, alpha, beta, n, elem_bytes) ? 1 : 0;
 }
 
-extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
-                             const cleave_device* devs, int32_t n_devs, int64_t granule,
-                             int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
-                             int32_t* tile_device, double* cost) {
+namespace {
+
+int assign_impl(int64_t m, int64_t q, int64_t n, int32_t elem_bytes, const cleave_device* devs,
+                int32_t n_devs, int64_t granule, const Caches& cc, int32_t* n_bands, int64_t* band_h,
+                int32_t* n_cols, int64_t* col_w, int32_t* tile_device, double* cost) {
   if (!devs || !n_bands || !band_h || !n_cols || !col_w || !tile_device || !cost) return CLEAVE_EINVAL;
   if (n_devs < 1 || granule < 1 || !sizes_ok(m, q, n, elem_bytes)) return CLEAVE_EINVAL;
   for (int32_t k = 0; k < n_devs; ++k)
@@ -152,14 +195,14 @@ extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes
     double t_hi = 1e-9;
     bool ok = false;
     for (int i = 0; i < 80 && !ok; ++i) {
-      ok = build_layout(m, q, n, elem_bytes, devs, n_devs, granule, t_hi, &found);
+      ok = build_layout(m, q, n, elem_bytes, devs, n_devs, granule, t_hi, cc, &found);
       if (!ok) t_hi *= 2.0;
     }
     if (!ok) return CLEAVE_EINVAL;   // the memory capacities admit no cover
     double lo = 0.0, hi = t_hi;
     for (int i = 0; i < 64; ++i) {
       const double mid = (lo + hi) / 2.0;
-      if (build_layout(m, q, n, elem_bytes, devs, n_devs, granule, mid, &trial)) {
+      if (build_layout(m, q, n, elem_bytes, devs, n_devs, granule, mid, cc, &trial)) {
         hi = mid;
         std::swap(found, trial);
       } else {
@@ -168,10 +211,23 @@ extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes
     }
     double worst = 0.0;
     size_t t = 0;
-    for (size_t band = 0; band < found.band_h.size(); ++band)
-      for (int32_t c = 0; c < found.n_cols[band]; ++c, ++t)
-        worst = std::max(worst, cost_of(devs[found.owner[t]], found.band_h[band], found.col_w[t],
-                                        found.band_h[band], found.col_w[t], n, elem_bytes));
+    int64_t r_lo = 0;
+    for (size_t band = 0; band < found.band_h.size(); ++band) {
+      int64_t c_lo = 0;
+      const int64_t h = found.band_h[band];
+      for (int32_t c = 0; c < found.n_cols[band]; ++c, ++t) {
+        const int64_t w = found.col_w[t];
+        int64_t af = h, bf = w;
+        if (cc.cached) {
+          const int64_t* ch = cc.cached + 4 * static_cast<int64_t>(found.owner[t]);
+          af = h - overlap(cc.row0 + r_lo, cc.row0 + r_lo + h, ch[0], ch[1]);
+          bf = w - overlap(cc.col0 + c_lo, cc.col0 + c_lo + w, ch[2], ch[3]);
+        }
+        worst = std::max(worst, cost_of(devs[found.owner[t]], h, w, af, bf, n, elem_bytes));
+        c_lo += w;
+      }
+      r_lo += h;
+    }
     *n_bands = static_cast<int32_t>(found.band_h.size());
     std::copy(found.band_h.begin(), found.band_h.end(), band_h);
     std::copy(found.n_cols.begin(), found.n_cols.end(), n_cols);
@@ -182,4 +238,33 @@ extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes
     return CLEAVE_ENOMEM;
   }
   return CLEAVE_OK;
+}
+
+}  // namespace
+
+extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                             const cleave_device* devs, int32_t n_devs, int64_t granule,
+                             int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
+                             int32_t* tile_device, double* cost) {
+  return assign_impl(m, q, n, elem_bytes, devs, n_devs, granule, Caches{}, n_bands, band_h, n_cols,
+                     col_w, tile_device, cost);
+}
+
+extern "C" int cleave_reassign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                               const cleave_device* devs, int32_t n_devs, int64_t granule,
+                               int64_t row0, int64_t col0, const int64_t* cached,
+                               const double* mem_used, int32_t* n_bands, int64_t* band_h,
+                               int32_t* n_cols, int64_t* col_w, int32_t* tile_device, double* cost) {
+  if (!cached || !mem_used || row0 < 0 || col0 < 0 || n_devs < 1) return CLEAVE_EINVAL;
+  for (int32_t k = 0; k < n_devs; ++k) {
+    const int64_t* c = cached + 4 * static_cast<int64_t>(k);
+    if (c[0] < 0 || c[1] < c[0] || c[2] < 0 || c[3] < c[2] || !(mem_used[k] >= 0.0)) return CLEAVE_EINVAL;
+  }
+  Caches cc;
+  cc.cached = cached;
+  cc.mem_used = mem_used;
+  cc.row0 = row0;
+  cc.col0 = col0;
+  return assign_impl(m, q, n, elem_bytes, devs, n_devs, granule, cc, n_bands, band_h, n_cols, col_w,
+                     tile_device, cost);
 }

@@ -173,3 +173,83 @@ def test_heuristic_stays_close_to_the_area_lower_bound_on_seeded_fleets(m, q, n,
     check_layout(m, q, n, 2, devs, g, res)
     lb = area_lower_bound(m, q, n, 2, devs, res[3])
     assert lb <= res[3] <= 1.35 * lb, (res[3], lb)
+
+
+# ---- churn re-solve (Sec. 4.2): cache-aware downlink, survivors only ----------
+
+def test_resolve_without_useful_caches_equals_the_cold_start():
+    rng = np.random.default_rng(3)
+    devs = [sc.Device(10 ** rng.uniform(5, 7), 10 ** rng.uniform(5, 7), 0.01, 0.01, 10 ** rng.uniform(11, 13), 1e12)
+            for _ in range(6)]
+    far = [(10 ** 6, 10 ** 6 + 5, 10 ** 6, 10 ** 6 + 5)] * 6          # nothing of the rectangle is cached
+    cold = sc.assign(512, 384, 256, 2, devs, 64)
+    warm = sc.assign(512, 384, 256, 2, devs, 64, origin=(1024, 2048), cached=far, mem_used=[0.0] * 6)
+    assert cold == warm
+
+
+def test_resolve_prefers_the_device_that_already_holds_the_rows_and_columns():
+    # two identical downlink-bound devices; device 1 holds every row and column of the rectangle
+    a = sc.Device(1e6, 1e9, 0.0, 0.0, 1e15, 1e12)
+    devs = [a, sc.Device(1e6, 1e9, 0.0, 0.0, 1e15, 1e12)]
+    cached = [(0, 0, 0, 0), (100, 100 + 256, 500, 500 + 256)]
+    res = sc.assign(256, 256, 512, 2, devs, 64, origin=(100, 500), cached=cached, mem_used=[0.0, 0.0])
+    check = [k for row in res[2] for k in row]
+    assert check == [1]                                  # the whole rectangle goes to the holder
+    assert res[3] == sc.shard_cost(devs[1], 256, 256, 512, 2, 0, 0) < sc.shard_cost(devs[0], 256, 256, 512, 2)
+    # the reported cost is the cache-aware one
+    cold = sc.assign(256, 256, 512, 2, devs, 64)
+    assert res[3] < cold[3]
+
+
+def test_resolve_respects_memory_already_in_use():
+    n, b = 256, 2
+    need = 64 * n * b * 2 + 64 * 64 * b                  # a fresh 64 x 64 shard
+    devs = [sc.Device(1e9, 1e9, 0.0, 0.0, 1e12, 2 * need) for _ in range(4)]
+    none = [(0, 0, 0, 0)] * 4
+    res = sc.assign(128, 128, n, b, devs, 64, cached=none, mem_used=[need] * 4)
+    assert all(h == 64 for h in res[0]) and all(w == 64 for ws in res[1] for w in ws)     # room for one more each
+    with pytest.raises(ValueError):
+        sc.assign(128, 128, n, b, devs, 64, cached=none, mem_used=[need + 1.0] * 4)
+    with pytest.raises(ValueError):
+        sc.assign(128, 128, n, b, devs, 64, cached=none)                                  # cached without mem_used
+
+
+def test_failure_of_one_device_is_repaired_with_an_exact_cover():
+    from workloads import draw_fleet
+    m, q, n, b, g = 2048, 1536, 1024, 2, 64
+    devs = [sc.Device(*d) for d in draw_fleet(12, 77)]
+    band_h, col_w, owner, cost = sc.assign(m, q, n, b, devs, g)
+    # rectangles of the cold-start layout
+    rects, r = {}, 0
+    for h, widths, owners in zip(band_h, col_w, owner):
+        c = 0
+        for w, k in zip(widths, owners):
+            rects[k] = (r, r + h, c, c + w)
+            c += w
+        r += h
+    failed = max(rects, key=lambda k: (rects[k][1] - rects[k][0]) * (rects[k][3] - rects[k][2]))
+    r0, r1, c0, c1 = rects[failed]
+    survivors = [k for k in range(len(devs)) if k != failed]
+    cached = [rects.get(k, (0, 0, 0, 0)) for k in survivors]
+    used = [0.0 if k not in rects else float(((rects[k][1] - rects[k][0]) + (rects[k][3] - rects[k][2])) * n * b +
+                                             (rects[k][1] - rects[k][0]) * (rects[k][3] - rects[k][2]) * b)
+            for k in survivors]
+    fix = sc.assign(r1 - r0, c1 - c0, n, b, [devs[k] for k in survivors], g, origin=(r0, c0), cached=cached, mem_used=used)
+    # paint: every output element is owned exactly once by a live device
+    paint = np.zeros((m // g, q // g), dtype=np.int32)
+    for k, (a0, a1, b0, b1) in rects.items():
+        if k != failed:
+            paint[a0 // g:-(-a1 // g), b0 // g:-(-b1 // g)] += 1
+    rr = r0
+    for h, widths in zip(fix[0], fix[1]):
+        cc = c0
+        for w in widths:
+            paint[rr // g:-(-(rr + h) // g), cc // g:-(-(cc + w) // g)] += 1
+            cc += w
+        assert cc == c1
+        rr += h
+    assert rr == r1 and np.all(paint == 1)
+    # neighbours in the failed device's band already hold its rows: re-solving with the caches is no slower
+    blind = sc.assign(r1 - r0, c1 - c0, n, b, [devs[k] for k in survivors], g, cached=[(0, 0, 0, 0)] * len(survivors),
+                      mem_used=used)
+    assert fix[3] <= blind[3]

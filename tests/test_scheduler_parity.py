@@ -70,3 +70,41 @@ def test_assignment_rejects_bad_input_and_infeasible_memory():
     bad = [cleave.Device(0.0, 1e6, 0.0, 0.0, 1e12, 1e9)]
     with pytest.raises(cleave.CleaveError):
         cleave.assign(64, 64, 64, 2, bad, 8)
+
+
+@pytest.mark.parametrize("m,q,n,k,g,seed", [(2048, 1536, 1024, 12, 64, 77), (4096, 4096, 4096, 40, 64, 5),
+                                            (1000, 777, 333, 9, 16, 9), (131072, 4096, 4096, 256, 128, 21)])
+def test_churn_resolve_is_identical_to_the_oracles(m, q, n, k, g, seed):
+    """Cold start, failure of the device with the largest shard, re-solve over the
+    survivors with their caches: layouts and costs equal the oracle's."""
+    fleet = draw_fleet(k, seed)
+    lib, ora = both(fleet)
+    band_h, col_w, owner, _ = sc.assign(m, q, n, 2, ora, g)
+    rects, r = {}, 0
+    for h, widths, owners in zip(band_h, col_w, owner):
+        c = 0
+        for w, dev in zip(widths, owners):
+            rects[dev] = (r, r + h, c, c + w)
+            c += w
+        r += h
+    failed = max(rects, key=lambda d: (rects[d][1] - rects[d][0]) * (rects[d][3] - rects[d][2]))
+    r0, r1, c0, c1 = rects[failed]
+    alive = [d for d in range(k) if d != failed]
+    cached = [rects.get(d, (0, 0, 0, 0)) for d in alive]
+    used = [0.0 if d not in rects else float(((rects[d][1] - rects[d][0]) + (rects[d][3] - rects[d][2])) * n * 2 +
+                                             (rects[d][1] - rects[d][0]) * (rects[d][3] - rects[d][2]) * 2)
+            for d in alive]
+    ref = sc.assign(r1 - r0, c1 - c0, n, 2, [ora[d] for d in alive], g, origin=(r0, c0), cached=cached, mem_used=used)
+    got = cleave.assign(r1 - r0, c1 - c0, n, 2, [lib[d] for d in alive], g, origin=(r0, c0), cached=cached,
+                        mem_used=used)
+    assert got[0] == ref[0] and got[1] == ref[1] and got[2] == ref[2] and got[3] == ref[3]
+
+
+def test_resolve_rejects_bad_caches():
+    lib, _ = both(draw_fleet(2, 1))
+    with pytest.raises(cleave.CleaveError):
+        cleave.assign(64, 64, 64, 2, lib, 8, cached=[(0, 0, 0, 0)], mem_used=[0.0, 0.0])
+    with pytest.raises(cleave.CleaveError):
+        cleave.assign(64, 64, 64, 2, lib, 8, cached=[(5, 2, 0, 0), (0, 0, 0, 0)], mem_used=[0.0, 0.0])
+    with pytest.raises(cleave.CleaveError):
+        cleave.assign(64, 64, 64, 2, lib, 8, cached=[(0, 0, 0, 0)] * 2, mem_used=[-1.0, 0.0])
