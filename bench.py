@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c5"])
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
@@ -101,7 +101,14 @@ def main():
         for name, t in ((g.a, A), (g.b, B)):
             if name not in dev:
                 dev[name] = t.cuda()
-        plan = cleave.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
+        if args.config == "c4":
+            # heterogeneous guillotine tiling with a K-split per tile, drawn per GEMM
+            from workloads import draw_explicit_tiling
+            from workloads.configs import C4_TILING_SEED
+            band_h, col_w, ks = draw_explicit_tiling(g.M, g.N, g.K, C4_TILING_SEED + gid)
+            plan = cleave.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
+        else:
+            plan = cleave.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
         plan.upload()
         gemms.append((g, plan, dev[g.a], dev[g.b]))
     # One partial workspace per DAG level (GEMMs of a level are independent and
@@ -198,9 +205,10 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {
-            "workload": "%s: layer fwd+bwd, %d GEMMs, %d tasks, uniform %dx%d tiles, K-split %d" % (
-                cfg.name, len(gemms), sum(p.num_tasks for _, p, _, _ in gemms),
-                cfg.tile_m, cfg.tile_n, cfg.ksplit),
+            "workload": ("%s: layer fwd+bwd, %d GEMMs, %d tasks, " % (
+                cfg.name, len(gemms), sum(p.num_tasks for _, p, _, _ in gemms))) + (
+                "heterogeneous tiles (edges 128..1024), K-split 1..8 per tile" if args.config == "c4" else
+                "uniform %dx%d tiles, K-split %d" % (cfg.tile_m, cfg.tile_n, cfg.ksplit)),
             "tile": [cfg.tile_m, cfg.tile_n], "ksplit": cfg.ksplit, "seed": cfg.seed,
         },
         "layer_fwd_bwd_ms": round(ms_per_step, 4),
