@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "86a2ed9f7266b6c260456f0ffc0615dd70c02ac5ccd33254fb48dc617789c117",
-    "execute_bytes_per_launch": (2.0 * 243907 + 395020) * 1024,
+    "sources_sha256": "848551b82854d0d45deed1c719258b00e6f62d659b15300f03c420cd29985090",
+    "execute_bytes_per_launch": (2.0 * 243920 + 394338) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
 }
 
@@ -44,7 +44,7 @@ def kernel_sources_digest():
     import hashlib
     csrc = os.path.join(ROOT, "paper_2512_22142_amd", "csrc")
     h = hashlib.sha256()
-    for name in ("execute.hip", "execute_direct.hip", "kernels.h", "plan.cpp", "plan_internal.h", "reduce.hip"):
+    for name in ("execute.hip", "execute_direct.hip", "kernels.h", "plan.cpp", "plan_internal.h", "reduce.hip", "tile_store.h"):
         with open(os.path.join(csrc, name), "rb") as f:
             h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()

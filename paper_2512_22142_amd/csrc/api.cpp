@@ -259,7 +259,6 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   for (int c = 0; c < cleave::kNumTileClasses; ++c) {
     if (counts[c] == 0) continue;
     cleave::ExecuteArgs args{};
-    args.tasks = plan->d_tasks;
     args.items = d_lists[c];
     args.n_items = counts[c];
     args.A = A;

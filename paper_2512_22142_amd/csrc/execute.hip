@@ -227,24 +227,20 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
 
   for (int64_t it = blockIdx.x; it < args.n_items; it += gridDim.x) {
     const WorkItem item = args.items[it];
-    const cleave_task task = args.tasks[item.task];
-    const uint32_t sub_cols = (task.n_len + TN - 1) / TN;
-    const uint32_t sub_m = item.sub / sub_cols;
-    const uint32_t sub_n = item.sub - sub_m * sub_cols;
-    const int m_valid = min(static_cast<int>(task.m_len - sub_m * TM), TM);
-    const int n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
-    const int64_t m_base = static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * TM;
-    const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * TN;
-    const int k_len = static_cast<int>(task.k_len);
+    const int m_valid = static_cast<int>(item.m_valid);
+    const int n_valid = static_cast<int>(item.n_valid);
+    const int64_t m_base = item.m_base;
+    const int64_t n_base = item.n_base;
+    const int k_len = static_cast<int>(item.k_len);
 
     const unsigned char* a_ptr =
         static_cast<const unsigned char*>(args.A) +
-        (batch_offset(task.gemm_id, args.batch_inner, args.a_outer, args.a_inner) + m_base * a_rs +
-         static_cast<int64_t>(task.k0) * a_ks) * EB;
+        (batch_offset(item.gemm_id, args.batch_inner, args.a_outer, args.a_inner) + m_base * a_rs +
+         static_cast<int64_t>(item.k0) * a_ks) * EB;
     const unsigned char* b_ptr =
         static_cast<const unsigned char*>(args.B) +
-        (batch_offset(task.gemm_id, args.batch_inner, args.b_outer, args.b_inner) + n_base * b_rs +
-         static_cast<int64_t>(task.k0) * b_ks) * EB;
+        (batch_offset(item.gemm_id, args.batch_inner, args.b_outer, args.b_inner) + n_base * b_rs +
+         static_cast<int64_t>(item.k0) * b_ks) * EB;
 
     f32x16 acc[MB][NB];
 #pragma unroll
@@ -345,8 +341,8 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
 
     const int row0 = wm * WTM + lh * 4;
     const int col0 = wn * WTN + l32;
-    store_tile<MB, NB>(acc, tile_target(args, task, sub_m, sub_n, TM, TN), args.C && args.c_bf16, row0,
-                       col0, m_valid, n_valid, m_valid == TM && n_valid == TN);
+    store_tile<MB, NB>(acc, tile_target(args, item), args.C && args.c_bf16, row0, col0, m_valid,
+                       n_valid, m_valid == TM && n_valid == TN);
   }
 }
 

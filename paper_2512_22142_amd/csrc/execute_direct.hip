@@ -203,25 +203,36 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     TileTarget out;               // where this sub-tile's accumulators go
     int steps, m_valid, n_valid;
   };
-  auto load_ctx = [&](int64_t it) -> ItemCtx {
-    const WorkItem item = args.items[it];
-    const cleave_task task = args.tasks[item.task];
-    const uint32_t sub_cols = (task.n_len + TN - 1) / TN;
-    const uint32_t sub_m = item.sub / sub_cols;
-    const uint32_t sub_n = item.sub - sub_m * sub_cols;
-    const int64_t m_base = static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * TM;
-    const int64_t n_base = static_cast<int64_t>(task.n0) + static_cast<int64_t>(sub_n) * TN;
+  // A work item record into scalar registers.  The table is never written by
+  // this kernel: read through the constant address space, a wave-uniform
+  // address becomes scalar loads whose completion the compiler tracks, even
+  // though the kernel also stores to global memory.
+  auto load_item = [&](int64_t idx) -> WorkItem {
+    typedef const __attribute__((address_space(4))) u32x4* const_words;
+    const_words src = (const_words)(args.items + idx);
+    uint32_t words[12];
+#pragma unroll
+    for (int v = 0; v < 3; ++v) {
+      const u32x4 q = src[v];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) words[4 * v + e] = q[e];
+    }
+    WorkItem w;
+    __builtin_memcpy(&w, words, sizeof(w));
+    return w;
+  };
+  auto make_ctx = [&](const WorkItem& w) -> ItemCtx {
     ItemCtx c;
-    c.m_valid = min(static_cast<int>(task.m_len - sub_m * TM), TM);
-    c.n_valid = min(static_cast<int>(task.n_len - sub_n * TN), TN);
-    c.steps = static_cast<int>(task.k_len) / S::BK;
+    c.m_valid = static_cast<int>(w.m_valid);
+    c.n_valid = static_cast<int>(w.n_valid);
+    c.steps = static_cast<int>(w.k_len) / S::BK;
     c.a_ptr = static_cast<const unsigned char*>(args.A) +
-              (batch_offset(task.gemm_id, args.batch_inner, args.a_outer, args.a_inner) +
-               m_base * a_rs + static_cast<int64_t>(task.k0) * a_ks) * 2;
+              (batch_offset(w.gemm_id, args.batch_inner, args.a_outer, args.a_inner) +
+               static_cast<int64_t>(w.m_base) * a_rs + static_cast<int64_t>(w.k0) * a_ks) * 2;
     c.b_ptr = static_cast<const unsigned char*>(args.B) +
-              (batch_offset(task.gemm_id, args.batch_inner, args.b_outer, args.b_inner) +
-               n_base * b_rs + static_cast<int64_t>(task.k0) * b_ks) * 2;
-    c.out = tile_target(args, task, sub_m, sub_n, TM, TN);
+              (batch_offset(w.gemm_id, args.batch_inner, args.b_outer, args.b_inner) +
+               static_cast<int64_t>(w.n_base) * b_rs + static_cast<int64_t>(w.k0) * b_ks) * 2;
+    c.out = tile_target(args, w);
     return c;
   };
   const int64_t a_step = a_ks * S::BK * 2;    // bytes per K step
@@ -244,10 +255,15 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       if (st < c.steps) issue(c, st, st);
   };
 
-  int64_t it = blockIdx.x;
-  if (it >= args.n_items) return;
-  ItemCtx c = load_ctx(it);
+  // Work items are walked with the grid as stride.  The record of the next
+  // item is read (one level of scalar loads) at the start of this item's
+  // epilogue; holding it in registers across the K loop instead cost more in
+  // spills than the load latency it hid.
+  const int64_t stride = gridDim.x;
+  if (static_cast<int64_t>(blockIdx.x) >= args.n_items) return;
+  ItemCtx c = make_ctx(load_item(blockIdx.x));
   fill_ring(c);
+  int64_t it_next = static_cast<int64_t>(blockIdx.x) + stride;
   // True when this item's ring fill was followed by the previous item's full
   // epilogue: more stores than the vector-memory counter can hold (63) were
   // issued after those loads, and the counter retires in issue order, so the
@@ -255,10 +271,6 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   bool fill_landed = false;
 
   for (;;) {
-    const int64_t it_next = it + gridDim.x;
-    const bool has_next = it_next < args.n_items;
-    ItemCtx nx = c;
-    if (has_next) nx = load_ctx(it_next);
     const int steps = c.steps;
 
     f32x16 acc[MB][NB];
@@ -363,9 +375,9 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         sub(int_c<1>{});
         sub(int_c<2>{});
       }
-      if (fill_landed && s + 1 < STAGES) {
-        // step s+1 belongs to the ring fill: nothing to wait for, and no reason
-        // to wait for the previous item's stores either
+      if ((fill_landed && s + 1 < STAGES) || s + 1 >= steps) {
+        // step s+1 belongs to the ring fill, or there is no step s+1: nothing to
+        // wait for, and no reason to wait for the previous item's stores either
         CLEAVE_WAIT_BARRIER(63);
       } else if (s + STAGES - 1 < steps) {
         CLEAVE_WAIT_BARRIER((STAGES - 2) * LPS);
@@ -404,13 +416,16 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     const TileTarget target = c.out;
     const int m_valid = c.m_valid, n_valid = c.n_valid;
     const bool interior = m_valid == TM && n_valid == TN;
+    const bool has_next = it_next < args.n_items;
+    const ItemCtx nx = make_ctx(load_item(has_next ? it_next : it_next - stride));
     if (has_next) fill_ring(nx);
-    store_tile<MB, NB>(acc, target, args.C && args.c_bf16, row0, col0, m_valid, n_valid, interior);
+    const bool bf16_out = args.C && args.c_bf16;
+    store_tile<MB, NB>(acc, target, bf16_out, row0, col0, m_valid, n_valid, interior);
     if (!has_next) break;
-    static_assert(MB * NB * 16 >= 63, "a full epilogue must saturate the vector-memory counter");
-    fill_landed = interior;
+    // the shortcut of the next item's first waits needs at least 63 stores behind the ring fill
+    fill_landed = interior && full_tile_stores<MB, NB>() >= 63;
     c = nx;
-    it = it_next;
+    it_next += stride;
   }
 }
 

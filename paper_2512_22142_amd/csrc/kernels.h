@@ -10,8 +10,7 @@
 namespace cleave {
 
 struct ExecuteArgs {
-  const cleave_task* tasks;   // device task table
-  const WorkItem* items;      // device work items of one tile class
+  const WorkItem* items;      // device work items of one tile class (self-contained records)
   int64_t n_items;
   const void* A;
   const void* B;

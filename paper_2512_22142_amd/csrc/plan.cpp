@@ -70,9 +70,8 @@ void order_work_items(cleave_plan* p) {
     std::vector<Key> lists[kXcds];
     for (const WorkItem& w : source) {
       const cleave_task& t = p->tasks[w.task];
-      const uint32_t sub_cols = (t.n_len + tc - 1) / tc;
-      const uint32_t m = t.m0 + (w.sub / sub_cols) * tr;
-      const uint32_t n = t.n0 + (w.sub % sub_cols) * tc;
+      const uint32_t m = w.m_base;
+      const uint32_t n = w.n_base;
       const int rm = static_cast<int>(static_cast<uint64_t>(m) * gm / static_cast<uint64_t>(p->M));
       const int rn = static_cast<int>(static_cast<uint64_t>(n) * gn / static_cast<uint64_t>(p->N));
       // relative position of the chunk inside [0, K): tiles with different
@@ -236,10 +235,24 @@ void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<Wo
   const int cls = fine ? static_cast<int>(kTileSmall) : tile_class_of(t);
   const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
   const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
-  const uint64_t sm = (t.m_len + tr - 1) / tr;
-  const uint64_t sn = (t.n_len + tc - 1) / tc;
-  for (uint64_t s = 0; s < sm * sn; ++s)
-    out[cls].push_back(WorkItem{task_index, static_cast<uint32_t>(s)});
+  const uint32_t sm = (t.m_len + tr - 1) / tr;
+  const uint32_t sn = (t.n_len + tc - 1) / tc;
+  for (uint32_t i = 0; i < sm; ++i)
+    for (uint32_t j = 0; j < sn; ++j) {
+      WorkItem w{};
+      w.m_base = t.m0 + i * tr;
+      w.n_base = t.n0 + j * tc;
+      w.k0 = t.k0;
+      w.k_len = t.k_len;
+      w.m_valid = std::min(tr, t.m_len - i * tr);
+      w.n_valid = std::min(tc, t.n_len - j * tc);
+      w.out_ld = t.n_len;
+      w.gemm_id = t.gemm_id;
+      w.out_off = t.partial_off + static_cast<uint64_t>(i) * tr * t.n_len + static_cast<uint64_t>(j) * tc;
+      w.task = task_index;
+      w.sub = i * sn + j;
+      out[cls].push_back(w);
+    }
 }
 
 }  // namespace cleave

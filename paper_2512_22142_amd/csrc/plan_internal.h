@@ -34,14 +34,21 @@ inline int tile_class_of(const cleave_task& t) {
   return (t.m_len > 128 && t.n_len > 128) ? kTileLarge : kTileSmall;
 }
 
-// One unit of work of the execute kernel: a sub-tile of one task's output
-// block, computed over the task's whole chunk of the inner dimension.
-struct WorkItem {
-  uint32_t task;    // index into the task table
-  uint32_t sub;     // sub-tile index within the task's block, row-major over
-                    // ceil(m_len/tile_rows) x ceil(n_len/tile_cols) sub-tiles
+// One unit of work of the execute kernels: a sub-tile of one task's output
+// block, computed over the task's whole chunk of the inner dimension.  The
+// record carries everything a workgroup needs, so that one load -- issued well
+// ahead -- replaces the dependent pair "which task, then that task's record".
+struct alignas(16) WorkItem {
+  uint32_t m_base, n_base;    // first row / column of the sub-tile in the logical output
+  uint32_t k0, k_len;         // the task's chunk
+  uint32_t m_valid, n_valid;  // extent of the sub-tile (at most the class's tile)
+  uint32_t out_ld;            // row stride of the task's partial block (= its n_len)
+  uint32_t gemm_id;           // batch member (batched plans)
+  uint64_t out_off;           // element offset of the sub-tile's origin in the partial buffer
+  uint32_t task;              // index into the task table
+  uint32_t sub;               // sub-tile index within the task's block, row-major
 };
-static_assert(sizeof(WorkItem) == 8, "WorkItem is 8 bytes");
+static_assert(sizeof(WorkItem) == 48, "WorkItem is 48 bytes");
 
 // One unit of work of the reduce kernel: a run of rows of one output tile.
 struct ReduceItem {

@@ -25,18 +25,15 @@ struct TileTarget {
 // alpha x beta block).  Assemble mode: the block's place in the output matrix
 // itself (Sec. 3.2: the PS assembles the returned blocks) -- only meaningful
 // for tasks that cover the whole inner dimension.
-__device__ __forceinline__ TileTarget tile_target(const ExecuteArgs& args, const cleave_task& task,
-                                                  uint32_t sub_m, uint32_t sub_n, int TM, int TN) {
+__device__ __forceinline__ TileTarget tile_target(const ExecuteArgs& args, const WorkItem& w) {
   TileTarget t;
   if (args.C == nullptr) {
-    t.ld = task.n_len;
-    t.base = reinterpret_cast<unsigned char*>(args.partials + task.partial_off +
-                                              static_cast<int64_t>(sub_m) * TM * t.ld + sub_n * TN);
+    t.ld = w.out_ld;
+    t.base = reinterpret_cast<unsigned char*>(args.partials + w.out_off);
   } else {
     t.ld = args.ldc;
-    const int64_t off = batch_offset(task.gemm_id, args.batch_inner, args.c_outer, args.c_inner) +
-                        (static_cast<int64_t>(task.m0) + static_cast<int64_t>(sub_m) * TM) * t.ld +
-                        task.n0 + sub_n * TN;
+    const int64_t off = batch_offset(w.gemm_id, args.batch_inner, args.c_outer, args.c_inner) +
+                        static_cast<int64_t>(w.m_base) * t.ld + w.n_base;
     t.base = static_cast<unsigned char*>(args.C) + off * (args.c_bf16 ? 2 : 4);
   }
   return t;
@@ -89,10 +86,16 @@ __device__ __forceinline__ void store_blocks(const tile_f32x16 (&acc)[MB][NB], T
   }
 }
 
+// Number of store instructions a lane issues for a full sub-tile.
+template <int MB, int NB>
+__device__ __forceinline__ constexpr int full_tile_stores() {
+  return MB * NB * 16;
+}
+
 template <int MB, int NB>
 __device__ __forceinline__ void store_tile(const tile_f32x16 (&acc)[MB][NB], const TileTarget& t,
-                                           bool bf16, int row0, int col0, int m_valid, int n_valid,
-                                           bool interior) {
+                                           bool bf16, int row0, int col0, int m_valid,
+                                           int n_valid, bool interior) {
   if (!bf16) {
     float* tp = reinterpret_cast<float*>(t.base) + row0 * t.ld + col0;
     store_blocks<MB, NB>(acc, tp, t.ld, row0, col0, m_valid, n_valid, interior,

@@ -45,6 +45,29 @@ def test_assemble_equals_execute_plus_reduce_and_the_oracle(dtype, M, N, K, tm, 
     assert og.rel_frobenius(C.float().cpu().numpy(), og.gemm(opA, opB)) <= bar
 
 
+@pytest.mark.parametrize("pad,shift", [(24, 0), (25, 0), (24, 1), (25, 1)])
+def test_assemble_bf16_output_alignment_cases(pad, shift):
+    """bf16 C with an even / odd leading dimension and a 4-byte / 2-byte aligned
+    origin: the two-element and the one-element store paths give the same bits."""
+    M, N, K = 384, 320, 128
+    A, B = make_matrix(311, M, K, "bf16"), make_matrix(312, K, N, "bf16", std=0.02)
+    plan = cleave.plan_uniform(M, N, K, 256, 256, 1)
+    dA, dB = A.cuda(), B.cuda()
+    ld = N + pad
+    flat = torch.full((M * ld + 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    wide = flat[shift:shift + M * ld].view(M, ld)
+    C = wide[:, :N]
+    cleave.execute_assemble(plan, dA, dB, C)
+    parts = torch.empty(plan.partial_elems, dtype=torch.float32, device="cuda")
+    C2 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    cleave.execute(plan, dA, dB, parts)
+    cleave.reduce(plan, parts, C2)
+    torch.cuda.synchronize()
+    assert torch.equal(C.contiguous().view(torch.int16), C2.view(torch.int16))
+    assert bool(torch.isnan(wide[:, N:].float()).all())
+    assert bool(torch.isnan(flat[:shift].float()).all()) and bool(torch.isnan(flat[shift + M * ld:].float()).all())
+
+
 def test_assemble_subset_writes_only_its_tiles():
     M, N, K = 512, 384, 128
     A, B = make_matrix(303, M, K, "bf16"), make_matrix(304, K, N, "bf16", std=0.02)
