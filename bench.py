@@ -171,6 +171,10 @@ def main():
         red_ms[i] += e1.elapsed_time(e2)
     exec_ms = [x / args.steps for x in exec_ms]
     red_ms = [x / args.steps for x in red_ms]
+    # each step on its own: first event of the step to its last
+    n_g = len(gemms)
+    step_ms = sorted(events[k * n_g][1].elapsed_time(events[k * n_g + n_g - 1][3]) for k in range(args.steps))
+    step_median = (step_ms[(len(step_ms) - 1) // 2] + step_ms[len(step_ms) // 2]) / 2
 
     flops = [g.flops for g, _, _, _ in gemms]
     red_bytes = [plan.partial_elems * 4 + g.M * g.N * 4 for g, plan, _, _ in gemms]
@@ -212,6 +216,8 @@ def main():
             "tile": [cfg.tile_m, cfg.tile_n], "ksplit": cfg.ksplit, "seed": cfg.seed,
         },
         "layer_fwd_bwd_ms": round(ms_per_step, 4),
+        "layer_fwd_bwd_ms_median": round(step_median, 4),
+        "layer_fwd_bwd_ms_min": round(step_ms[0], 4),
         "execute_ms": round(exec_total_ms, 4),
         "reduce_ms": round(red_total_ms, 4),
         "execute_tflops": round(exec_tflops, 2),
