@@ -112,8 +112,9 @@ int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_bands, const
  * level).  Member g contributes the uniform plan of a single GEMM with
  * gemm_id = g: tile ids restart at 0, partial offsets run on through the whole
  * list.  The plan is used with cleave_execute_batched / cleave_reduce_batched
- * (the plain calls return CLEAVE_EINVAL on it, and the batched calls on a
- * plain plan).  CLEAVE_EINVAL as for cleave_plan_uniform, or n_batch < 1. */
+ * (members addressed by strides) or cleave_execute_grouped /
+ * cleave_reduce_grouped (one pointer per member); the plain calls return
+ * CLEAVE_EINVAL on it, and the batched and grouped calls on a plain plan.  CLEAVE_EINVAL as for cleave_plan_uniform, or n_batch < 1. */
 int cleave_plan_batched(int64_t M, int64_t N, int64_t K, int64_t tile_m, int64_t tile_n,
                         int32_t ksplit, int64_t n_batch, cleave_plan** out);
 
@@ -160,6 +161,23 @@ int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n
                            const void* B, int64_t ldb, int transB, int64_t b_outer, int64_t b_inner,
                            int64_t n_inner, int dtype, float* partials, void* hip_stream);
 
+/* Grouped form of cleave_execute: the same-shape GEMMs of one DAG level in one
+ * launch (Sec. 4.1: the GEMMs of a level are independent and are dispatched
+ * together, e.g. the Q, K and V projections).  plan: made by
+ * cleave_plan_batched with n_batch <= 8 members; n_members: must equal
+ * n_batch; A_list, B_list: host arrays of n_members device pointers (read
+ * during the call only), member g multiplies A_list[g] by B_list[g]
+ * (pointers may repeat: the projections of a level share their input).  All
+ * members share lda, transA, ldb, transB and dtype.  partials: one workspace of
+ * cleave_plan_partial_elems elements, member after member.  The bits of a
+ * block are those a single-GEMM plan of the same tiling gives for that member.
+ * CLEAVE_EINVAL: as for cleave_execute, a plain plan, more than 8 members,
+ * n_members != n_batch, a null or misaligned member pointer. */
+int cleave_execute_grouped(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                           int64_t n_members, const void* const* A_list, int64_t lda, int transA,
+                           const void* const* B_list, int64_t ldb, int transB,
+                           int dtype, float* partials, void* hip_stream);
+
 /* Execute for plans without K-splits (every task covers the whole inner
  * dimension, as in the paper's own decomposition, Sec. 4.1): each block is
  * already the finished piece of the output, so it is written straight to its
@@ -192,6 +210,12 @@ int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc
 int cleave_reduce_batched(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
                           int64_t c_outer, int64_t c_inner, int64_t n_inner,
                           int out_dtype, void* hip_stream);
+
+/* Grouped form of cleave_reduce, the counterpart of cleave_execute_grouped:
+ * member g's M x N result goes to C_list[g] (host array of n_members = n_batch
+ * device pointers), all with leading dimension ldc and element type out_dtype. */
+int cleave_reduce_grouped(cleave_plan* plan, const float* partials, int64_t n_members,
+                          void* const* C_list, int64_t ldc, int out_dtype, void* hip_stream);
 
 /* ---- aggregation feeding a PS-side streaming operator ---------------------
  * The paper keeps non-GEMM operators and the optimizer on the parameter

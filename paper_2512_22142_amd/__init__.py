@@ -27,12 +27,14 @@ _BINDING_NAMES = (
     "execute",
     "execute_assemble",
     "execute_batched",
+    "execute_grouped",
     "plan_batched",
     "plan_explicit",
     "plan_uniform",
     "reduce",
     "reduce_adam",
     "reduce_batched",
+    "reduce_grouped",
     "reduce_residual",
     "verify",
     "version",

@@ -37,6 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
+    "cleave_execute_grouped", "cleave_reduce_grouped",
 )
 
 
@@ -98,6 +99,11 @@ def _load():
     lib.cleave_execute_assemble.restype = ctypes.c_int
     lib.cleave_reduce_batched.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p]
     lib.cleave_reduce_batched.restype = ctypes.c_int
+    lib.cleave_execute_grouped.argtypes = [p, p, i64, i64, p, i64, ctypes.c_int, p, i64, ctypes.c_int,
+                                           ctypes.c_int, p, p]
+    lib.cleave_execute_grouped.restype = ctypes.c_int
+    lib.cleave_reduce_grouped.argtypes = [p, p, i64, p, i64, ctypes.c_int, p]
+    lib.cleave_reduce_grouped.restype = ctypes.c_int
     lib.cleave_reduce_residual.argtypes = [p, p, p, p, i64, ctypes.c_int, p]
     lib.cleave_reduce_residual.restype = ctypes.c_int
     f32 = ctypes.c_float
@@ -318,6 +324,47 @@ def reduce_batched(plan, partials, C, c_strides, n_inner, stream=None):
     _check(_lib.cleave_reduce_batched(plan._h, ctypes.c_void_p(partials.data_ptr()), c_ptr, ldc,
                                       int(c_strides[0]), int(c_strides[1]), int(n_inner),
                                       _dtype_code(C), _stream_ptr(stream)), "cleave_reduce_batched")
+
+
+def _member_pointers(tensors, what):
+    """Host array of the members' device pointers; checks that they share
+    dtype and leading dimension."""
+    lds = {_device_2d(t, what)[1] for t in tensors}
+    if len(lds) != 1 or len({t.dtype for t in tensors}) != 1:
+        raise ValueError("%s: members must share dtype and leading dimension" % what)
+    arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+    return arr, lds.pop()
+
+
+def execute_grouped(plan, A_list, B_list, partials, transA=0, transB=0, task_ids=None, stream=None):
+    """cleave_execute_grouped: member g of the batched plan multiplies A_list[g]
+    by B_list[g] (2-D device tensors; entries may repeat)."""
+    import torch
+    a_arr, lda = _member_pointers(A_list, "A_list")
+    b_arr, ldb = _member_pointers(B_list, "B_list")
+    if A_list[0].dtype != B_list[0].dtype:
+        raise TypeError("A and B must have the same dtype")
+    if len(A_list) != len(B_list):
+        raise ValueError("A_list and B_list must have one entry per member")
+    if partials.dtype != torch.float32 or not partials.is_cuda or not partials.is_contiguous() \
+            or partials.numel() < plan.partial_elems:
+        raise ValueError("partials must be a contiguous fp32 device tensor of partial_elems elements")
+    ids_ptr, n_ids = None, 0
+    if task_ids is not None:
+        ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+        ids_ptr, n_ids = ctypes.c_void_p(ids.ctypes.data), len(ids)
+    _check(_lib.cleave_execute_grouped(plan._h, ids_ptr, n_ids, len(A_list), a_arr, lda, int(transA), b_arr, ldb,
+                                       int(transB), _dtype_code(A_list[0]),
+                                       ctypes.c_void_p(partials.data_ptr()), _stream_ptr(stream)),
+           "cleave_execute_grouped")
+
+
+def reduce_grouped(plan, partials, C_list, stream=None):
+    """cleave_reduce_grouped: member g's result goes to C_list[g]."""
+    c_arr, ldc = _member_pointers(C_list, "C_list")
+    _check(_lib.cleave_reduce_grouped(plan._h, ctypes.c_void_p(partials.data_ptr()), len(C_list), c_arr, ldc,
+                                      _dtype_code(C_list[0]), _stream_ptr(stream)),
+           "cleave_reduce_grouped")
 
 
 def reduce_residual(plan, partials, R, C, stream=None):

@@ -127,7 +127,7 @@ const char* direct_kernel_name(int cls, int transA, int transB) {
 
 extern "C" int cleave_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" int cleave_version(void) { return 106; }
+extern "C" int cleave_version(void) { return 107; }
 
 extern "C" int cleave_plan_upload(cleave_plan* plan) {
   if (!plan) return CLEAVE_EINVAL;
@@ -143,12 +143,47 @@ extern "C" void cleave_plan_destroy(cleave_plan* plan) {
 
 namespace {
 
-// Strides of a batched call, in elements; n_inner = 0 for a plain plan.
-struct BatchStrides {
-  int64_t n_inner = 0;
-  int64_t a_outer = 0, a_inner = 0, b_outer = 0, b_inner = 0;
-  int64_t c_outer = 0, c_inner = 0;   // assemble mode only
+// How a batched call finds its members' matrices (element offsets from the
+// base pointers); all zero for a plain plan.
+struct BatchLayout {
+  cleave::BatchShape shape{0, 0};
+  cleave::MemberOffsets a{}, b{};
+  cleave::MemberOffsets c{};   // assemble mode and reduce only
 };
+
+// Every member offset is a multiple of `e` elements.
+bool offsets_multiple_of(const cleave::MemberOffsets& at, const cleave::BatchShape& shape, int64_t e) {
+  if (shape.n_group == 0) return at.outer % e == 0 && at.inner % e == 0;
+  for (uint32_t g = 0; g < shape.n_group; ++g)
+    if (at.table[g] % e != 0) return false;
+  return true;
+}
+
+BatchLayout strided_layout(int64_t n_inner, int64_t a_outer, int64_t a_inner, int64_t b_outer,
+                           int64_t b_inner, int64_t c_outer, int64_t c_inner) {
+  BatchLayout bl;
+  bl.shape.batch_inner = static_cast<uint32_t>(n_inner);
+  bl.a.outer = a_outer;
+  bl.a.inner = a_inner;
+  bl.b.outer = b_outer;
+  bl.b.inner = b_inner;
+  bl.c.outer = c_outer;
+  bl.c.inner = c_inner;
+  return bl;
+}
+
+// Grouped launch: members given by one pointer each.  list[0] becomes the base
+// pointer, the others element offsets from it.
+int group_offsets(const void* const* list, int64_t n, int elem_bytes, cleave::MemberOffsets* at,
+                  const void** base) {
+  if (!list || n < 1 || n > cleave::kMaxGroup) return CLEAVE_EINVAL;
+  for (int64_t g = 0; g < n; ++g)
+    if (!list[g] || !aligned(list[g], elem_bytes)) return CLEAVE_EINVAL;
+  *base = list[0];
+  for (int64_t g = 0; g < n; ++g)
+    at->table[g] = (reinterpret_cast<intptr_t>(list[g]) - reinterpret_cast<intptr_t>(list[0])) / elem_bytes;
+  return CLEAVE_OK;
+}
 
 // Assemble mode: blocks go to their place in C instead of the partial buffer.
 struct AssembleTarget {
@@ -159,7 +194,7 @@ struct AssembleTarget {
 
 int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, const void* A,
                  int64_t lda, int transA, const void* B, int64_t ldb, int transB, int dtype,
-                 float* partials, const BatchStrides& bs, void* hip_stream,
+                 float* partials, const BatchLayout& bl, void* hip_stream,
                  const AssembleTarget& asm_to = AssembleTarget{}) {
   if (!plan || !A || !B || (!partials && !asm_to.C)) return CLEAVE_EINVAL;
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
@@ -214,8 +249,7 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
                    lda % e == 0 && ldb % e == 0 && aligned(A, 16) && aligned(B, 16) &&
                    // in-tile byte offsets are kept in 32 bits
                    lda * eb < (int64_t{1} << 22) && ldb * eb < (int64_t{1} << 22) &&
-                   bs.a_outer % e == 0 && bs.a_inner % e == 0 && bs.b_outer % e == 0 &&
-                   bs.b_inner % e == 0;
+                   offsets_multiple_of(bl.a, bl.shape, e) && offsets_multiple_of(bl.b, bl.shape, e);
 
   const cleave::WorkItem* d_lists[cleave::kNumTileClasses] = {plan->d_items[0], plan->d_items[1]};
   int64_t counts[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items[0].size()),
@@ -268,16 +302,13 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     args.transA = transA;
     args.transB = transB;
     args.partials = partials;
-    args.batch_inner = static_cast<uint32_t>(bs.n_inner);
-    args.a_outer = bs.a_outer;
-    args.a_inner = bs.a_inner;
-    args.b_outer = bs.b_outer;
-    args.b_inner = bs.b_inner;
+    args.batch = bl.shape;
+    args.a_at = bl.a;
+    args.b_at = bl.b;
+    args.c_at = bl.c;
     args.C = asm_to.C;
     args.ldc = asm_to.ldc;
     args.c_bf16 = asm_to.out_dtype == CLEAVE_BF16 ? 1 : 0;
-    args.c_outer = bs.c_outer;
-    args.c_inner = bs.c_inner;
     const bool direct = vec && dtype == CLEAVE_BF16 &&
                         (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
     if (direct) {
@@ -311,7 +342,7 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
                               int transB, int dtype, float* partials, void* hip_stream) {
   if (plan && plan->batch > 0) return CLEAVE_EINVAL;   // batched plans use the batched call
   return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials,
-                      BatchStrides{}, hip_stream);
+                      BatchLayout{}, hip_stream);
 }
 
 extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
@@ -323,13 +354,28 @@ extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids
   if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
     return CLEAVE_EINVAL;
   if (a_outer < 0 || a_inner < 0 || b_outer < 0 || b_inner < 0) return CLEAVE_EINVAL;
-  BatchStrides bs;
-  bs.n_inner = n_inner;
-  bs.a_outer = a_outer;
-  bs.a_inner = a_inner;
-  bs.b_outer = b_outer;
-  bs.b_inner = b_inner;
-  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials, bs,
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials,
+                      strided_layout(n_inner, a_outer, a_inner, b_outer, b_inner, 0, 0), hip_stream);
+}
+
+extern "C" int cleave_execute_grouped(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                                      int64_t n_members, const void* const* A_list, int64_t lda,
+                                      int transA,
+                                      const void* const* B_list, int64_t ldb, int transB, int dtype,
+                                      float* partials, void* hip_stream) {
+  if (!plan || plan->batch < 1 || plan->batch > cleave::kMaxGroup || n_members != plan->batch)
+    return CLEAVE_EINVAL;
+  if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  const int eb = dtype == CLEAVE_BF16 ? 2 : 4;
+  BatchLayout bl;
+  bl.shape.n_group = static_cast<uint32_t>(plan->batch);
+  const void* A = nullptr;
+  const void* B = nullptr;
+  int rc = group_offsets(A_list, plan->batch, eb, &bl.a, &A);
+  if (rc != CLEAVE_OK) return rc;
+  rc = group_offsets(B_list, plan->batch, eb, &bl.b, &B);
+  if (rc != CLEAVE_OK) return rc;
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials, bl,
                       hip_stream);
 }
 
@@ -345,19 +391,13 @@ extern "C" int cleave_execute_assemble(cleave_plan* plan, const int64_t* task_id
   // a block is the finished output only if its task covers the whole inner dimension
   for (const cleave_task& t : plan->tasks)
     if (t.ksplit_cnt != 1) return CLEAVE_EINVAL;
-  BatchStrides bs;
+  BatchLayout bl;
   if (plan->batch > 0) {
     if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
       return CLEAVE_EINVAL;
     if (a_outer < 0 || a_inner < 0 || b_outer < 0 || b_inner < 0 || c_outer < 0 || c_inner < 0)
       return CLEAVE_EINVAL;
-    bs.n_inner = n_inner;
-    bs.a_outer = a_outer;
-    bs.a_inner = a_inner;
-    bs.b_outer = b_outer;
-    bs.b_inner = b_inner;
-    bs.c_outer = c_outer;
-    bs.c_inner = c_inner;
+    bl = strided_layout(n_inner, a_outer, a_inner, b_outer, b_inner, c_outer, c_inner);
   } else if (n_inner != 0 || a_outer || a_inner || b_outer || b_inner || c_outer || c_inner) {
     return CLEAVE_EINVAL;   // strides belong to batched plans
   }
@@ -365,7 +405,7 @@ extern "C" int cleave_execute_assemble(cleave_plan* plan, const int64_t* task_id
   to.C = C;
   to.ldc = ldc;
   to.out_dtype = out_dtype;
-  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, nullptr, bs,
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, nullptr, bl,
                       hip_stream, to);
 }
 
@@ -378,7 +418,7 @@ struct ReduceEpilogue {
 };
 
 int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, int out_dtype,
-                int64_t n_inner, int64_t c_outer, int64_t c_inner, void* hip_stream,
+                const BatchLayout& bl, void* hip_stream,
                 const ReduceEpilogue& epi = ReduceEpilogue{}) {
   if (!plan || !partials || !C) return CLEAVE_EINVAL;
   if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
@@ -391,7 +431,7 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   if (rc != CLEAVE_OK) return rc;
 
   bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
-             c_outer % 4 == 0 && c_inner % 4 == 0;
+             offsets_multiple_of(bl.c, bl.shape, 4);
   if (epi.residual) vec = vec && aligned(epi.residual, 4 * ob);
   if (epi.adam)
     vec = vec && aligned(epi.adam->m, 16) && aligned(epi.adam->v, 16) &&
@@ -403,9 +443,8 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   args.partials = partials;
   args.C = C;
   args.ldc = ldc;
-  args.batch_inner = static_cast<uint32_t>(n_inner);
-  args.c_outer = c_outer;
-  args.c_inner = c_inner;
+  args.batch = bl.shape;
+  args.c_at = bl.c;
   // one workgroup per reduce item (the kernel loops only if the grid is capped)
   const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20));
   if (epi.adam) {
@@ -427,7 +466,7 @@ extern "C" int cleave_reduce_residual(cleave_plan* plan, const float* partials, 
   if (!aligned(R, out_dtype == CLEAVE_BF16 ? 2 : 4)) return CLEAVE_EINVAL;
   ReduceEpilogue epi;
   epi.residual = R;
-  return reduce_impl(plan, partials, C, ldc, out_dtype, 0, 0, 0, hip_stream, epi);
+  return reduce_impl(plan, partials, C, ldc, out_dtype, BatchLayout{}, hip_stream, epi);
 }
 
 extern "C" int cleave_reduce_adam(cleave_plan* plan, const float* partials, float* w, float* m,
@@ -454,13 +493,13 @@ extern "C" int cleave_reduce_adam(cleave_plan* plan, const float* partials, floa
   ReduceEpilogue epi;
   epi.adam = &h;
   // the fp32 master weight takes C's place in the common checks (pointer, leading dimension)
-  return reduce_impl(plan, partials, w, ld, CLEAVE_F32, 0, 0, 0, hip_stream, epi);
+  return reduce_impl(plan, partials, w, ld, CLEAVE_F32, BatchLayout{}, hip_stream, epi);
 }
 
 extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
                              int out_dtype, void* hip_stream) {
   if (plan && plan->batch > 0) return CLEAVE_EINVAL;
-  return reduce_impl(plan, partials, C, ldc, out_dtype, 0, 0, 0, hip_stream);
+  return reduce_impl(plan, partials, C, ldc, out_dtype, BatchLayout{}, hip_stream);
 }
 
 extern "C" int cleave_reduce_batched(cleave_plan* plan, const float* partials, void* C, int64_t ldc,
@@ -470,7 +509,22 @@ extern "C" int cleave_reduce_batched(cleave_plan* plan, const float* partials, v
   if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
     return CLEAVE_EINVAL;
   if (c_outer < 0 || c_inner < 0) return CLEAVE_EINVAL;
-  return reduce_impl(plan, partials, C, ldc, out_dtype, n_inner, c_outer, c_inner, hip_stream);
+  return reduce_impl(plan, partials, C, ldc, out_dtype,
+                     strided_layout(n_inner, 0, 0, 0, 0, c_outer, c_inner), hip_stream);
+}
+
+extern "C" int cleave_reduce_grouped(cleave_plan* plan, const float* partials, int64_t n_members,
+                                     void* const* C_list, int64_t ldc, int out_dtype,
+                                     void* hip_stream) {
+  if (!plan || plan->batch < 1 || plan->batch > cleave::kMaxGroup || n_members != plan->batch)
+    return CLEAVE_EINVAL;
+  if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  BatchLayout bl;
+  bl.shape.n_group = static_cast<uint32_t>(plan->batch);
+  const void* C = nullptr;
+  const int rc = group_offsets(C_list, plan->batch, out_dtype == CLEAVE_BF16 ? 2 : 4, &bl.c, &C);
+  if (rc != CLEAVE_OK) return rc;
+  return reduce_impl(plan, partials, const_cast<void*>(C), ldc, out_dtype, bl, hip_stream);
 }
 
 namespace {

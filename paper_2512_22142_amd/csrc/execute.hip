@@ -235,11 +235,11 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
 
     const unsigned char* a_ptr =
         static_cast<const unsigned char*>(args.A) +
-        (batch_offset(item.gemm_id, args.batch_inner, args.a_outer, args.a_inner) + m_base * a_rs +
+        (member_offset(args.a_at, args.batch, item.gemm_id) + m_base * a_rs +
          static_cast<int64_t>(item.k0) * a_ks) * EB;
     const unsigned char* b_ptr =
         static_cast<const unsigned char*>(args.B) +
-        (batch_offset(item.gemm_id, args.batch_inner, args.b_outer, args.b_inner) + n_base * b_rs +
+        (member_offset(args.b_at, args.batch, item.gemm_id) + n_base * b_rs +
          static_cast<int64_t>(item.k0) * b_ks) * EB;
 
     f32x16 acc[MB][NB];

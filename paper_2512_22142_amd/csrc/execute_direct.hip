@@ -227,10 +227,10 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     c.n_valid = static_cast<int>(w.n_valid);
     c.steps = static_cast<int>(w.k_len) / S::BK;
     c.a_ptr = static_cast<const unsigned char*>(args.A) +
-              (batch_offset(w.gemm_id, args.batch_inner, args.a_outer, args.a_inner) +
+              (member_offset(args.a_at, args.batch, w.gemm_id) +
                static_cast<int64_t>(w.m_base) * a_rs + static_cast<int64_t>(w.k0) * a_ks) * 2;
     c.b_ptr = static_cast<const unsigned char*>(args.B) +
-              (batch_offset(w.gemm_id, args.batch_inner, args.b_outer, args.b_inner) +
+              (member_offset(args.b_at, args.batch, w.gemm_id) +
                static_cast<int64_t>(w.n_base) * b_rs + static_cast<int64_t>(w.k0) * b_ks) * 2;
     c.out = tile_target(args, w);
     return c;

@@ -9,6 +9,30 @@
 
 namespace cleave {
 
+// Most members a grouped launch (one table entry per member) can have.
+constexpr int kMaxGroup = 8;
+
+// Where batch member g's matrix starts, as an element offset from the base
+// pointer.  Strided batch (batch_inner > 0): member o * batch_inner + i at
+// o * outer + i * inner.  Grouped launch (n_group > 0): member g at table[g].
+// Plain plans have one member at offset 0.
+struct MemberOffsets {
+  int64_t outer, inner;
+  int64_t table[kMaxGroup];
+};
+
+struct BatchShape {
+  uint32_t batch_inner;
+  uint32_t n_group;
+};
+
+__host__ __device__ inline int64_t member_offset(const MemberOffsets& at, BatchShape b, uint32_t gemm_id) {
+  if (b.n_group != 0) return at.table[gemm_id];
+  if (b.batch_inner == 0) return 0;
+  const uint32_t o = gemm_id / b.batch_inner;
+  return static_cast<int64_t>(o) * at.outer + static_cast<int64_t>(gemm_id - o * b.batch_inner) * at.inner;
+}
+
 struct ExecuteArgs {
   const WorkItem* items;      // device work items of one tile class (self-contained records)
   int64_t n_items;
@@ -17,25 +41,16 @@ struct ExecuteArgs {
   int64_t lda, ldb;           // elements
   int transA, transB;
   float* partials;
-  // Batched plans (batch_inner > 0): task.gemm_id = o * batch_inner + i selects
-  // the operands at element offsets o * outer + i * inner from A and B.
-  uint32_t batch_inner;
-  int64_t a_outer, a_inner, b_outer, b_inner;
+  // Batched plans: task.gemm_id selects the member's operands (and, in
+  // assemble mode, its output) through these offsets.
+  BatchShape batch;
+  MemberOffsets a_at, b_at, c_at;
   // Assemble mode (C != nullptr): blocks go straight to their place in the
   // output matrix (fp32, or bf16 when c_bf16 != 0) instead of `partials`.
   void* C;
   int64_t ldc;
   int c_bf16;
-  int64_t c_outer, c_inner;
 };
-
-// Element offset of the operands of batch member `gemm_id` (0 for plain plans).
-__host__ __device__ inline int64_t batch_offset(uint32_t gemm_id, uint32_t batch_inner, int64_t outer,
-                                                int64_t inner) {
-  if (batch_inner == 0) return 0;
-  const uint32_t o = gemm_id / batch_inner;
-  return static_cast<int64_t>(o) * outer + static_cast<int64_t>(gemm_id - o * batch_inner) * inner;
-}
 
 // Enqueues the execute kernel for one tile class.  `vec` selects the 16-byte
 // load path (caller has checked alignment and divisibility).
@@ -59,8 +74,8 @@ struct ReduceArgs {
   const float* partials;
   void* C;
   int64_t ldc;                // elements
-  uint32_t batch_inner;       // as in ExecuteArgs; offsets apply to C
-  int64_t c_outer, c_inner;
+  BatchShape batch;           // as in ExecuteArgs; offsets apply to C
+  MemberOffsets c_at;
 };
 
 // Enqueues the aggregation kernel.  `vec` selects the float4 path.

@@ -25,6 +25,9 @@ bool valid_split(int64_t K, int64_t S) {
 }
 
 constexpr int kXcds = 8;
+// A batch member with at least this many work items (one per CU of the chip) is
+// spread over all XCDs instead of being kept on one.
+constexpr size_t kSpreadItems = 256;
 
 // The work items that run on an XCD at the same time (one per CU, 32 CUs) are
 // taken from a patch of kPatchRows x kPatchCols sub-tiles at one chunk of the
@@ -64,10 +67,16 @@ void order_work_items(cleave_plan* p) {
     const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
     const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
     struct Key {
-      uint32_t member, split, pm, pn, m, n;   // member: 0 unless the plan is a batch
+      uint32_t outer_member, split, pm, pn, inner_member, m, n;
       WorkItem item;
     };
     std::vector<Key> lists[kXcds];
+    // Batch members share no output.  Small members (fewer items than the
+    // chip has CUs) stay on one XCD each, member g on XCD g mod 8, one after
+    // the other.  Large members (the GEMMs of one DAG level) are spread over
+    // the XCDs like a single GEMM, and the members take turns patch by patch,
+    // so that an operand panel they share is still in L2 for the next one.
+    const bool member_per_xcd = p->batch > 0 && source.size() / static_cast<size_t>(p->batch) < kSpreadItems;
     for (const WorkItem& w : source) {
       const cleave_task& t = p->tasks[w.task];
       const uint32_t m = w.m_base;
@@ -77,18 +86,18 @@ void order_work_items(cleave_plan* p) {
       // relative position of the chunk inside [0, K): tiles with different
       // split counts still line up by where in K they work
       const uint32_t split = static_cast<uint32_t>(static_cast<uint64_t>(t.k0) * 64 / static_cast<uint64_t>(p->K));
-      // Batch members share no operands: a member stays on one XCD
-      // (member g on XCD g mod 8), members one after the other.
-      const int region = p->batch > 0 ? static_cast<int>(t.gemm_id % kXcds) : rm * gn + rn;
-      lists[region].push_back(Key{t.gemm_id, split, m / (kPatchRows * tr), n / (kPatchCols * tc), m, n, w});
+      const int region = member_per_xcd ? static_cast<int>(t.gemm_id % kXcds) : rm * gn + rn;
+      lists[region].push_back(Key{member_per_xcd ? t.gemm_id : 0u, split, m / (kPatchRows * tr),
+                                  n / (kPatchCols * tc), member_per_xcd ? 0u : t.gemm_id, m, n, w});
     }
     size_t longest = 0;
     for (auto& l : lists) {
       std::stable_sort(l.begin(), l.end(), [](const Key& a, const Key& b) {
-        if (a.member != b.member) return a.member < b.member;
+        if (a.outer_member != b.outer_member) return a.outer_member < b.outer_member;
         if (a.split != b.split) return a.split < b.split;
         if (a.pm != b.pm) return a.pm < b.pm;
         if (a.pn != b.pn) return a.pn < b.pn;
+        if (a.inner_member != b.inner_member) return a.inner_member < b.inner_member;
         if (a.m != b.m) return a.m < b.m;
         return a.n < b.n;
       });

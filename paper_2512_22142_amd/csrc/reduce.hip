@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args, Epi e
     const float* p0 = args.partials + task.partial_off + static_cast<uint64_t>(item.row0) * n_len;
     const uint32_t count = item.rows * n_len;
     const int64_t c_row0 = static_cast<int64_t>(task.m0) + item.row0;
-    const int64_t c_base = batch_offset(task.gemm_id, args.batch_inner, args.c_outer, args.c_inner) +
+    const int64_t c_base = member_offset(args.c_at, args.batch, task.gemm_id) +
                            c_row0 * args.ldc + task.n0;
 
     if constexpr (VEC) {

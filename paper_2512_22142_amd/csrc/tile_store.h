@@ -32,7 +32,7 @@ __device__ __forceinline__ TileTarget tile_target(const ExecuteArgs& args, const
     t.base = reinterpret_cast<unsigned char*>(args.partials + w.out_off);
   } else {
     t.ld = args.ldc;
-    const int64_t off = batch_offset(w.gemm_id, args.batch_inner, args.c_outer, args.c_inner) +
+    const int64_t off = member_offset(args.c_at, args.batch, w.gemm_id) +
                         static_cast<int64_t>(w.m_base) * t.ld + w.n_base;
     t.base = static_cast<unsigned char*>(args.C) + off * (args.c_bf16 ? 2 : 4);
   }

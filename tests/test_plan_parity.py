@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(cleave.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
-    assert cleave.version() == 106
+    assert cleave.version() == 107
     assert cleave.TASK_DTYPE.itemsize == planner.TASK_DTYPE.itemsize == 64
 
 
