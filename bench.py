@@ -34,9 +34,9 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "848551b82854d0d45deed1c719258b00e6f62d659b15300f03c420cd29985090",
-    "execute_bytes_per_launch": (2.0 * 243920 + 394338) * 1024,
-    "reduce_bytes_per_launch": (2.0 * 194738 + 97134) * 1024,
+    "sources_sha256": "11b5472c51c3019b13e72e065d70ff5514092795f45a5615506894f478cf8cb7",
+    "execute_bytes_per_launch": (2.0 * 243583 + 394338) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194739 + 97134) * 1024,
 }
 
 
@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--group-levels", action="store_true",
+                    help="one grouped launch per set of same-shape GEMMs of a DAG level (12 launches "
+                         "per c3 step instead of 21); measured: execute +1 %, reduce -3 %, step time equal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
@@ -127,18 +130,59 @@ def main():
 
     stream = torch.cuda.current_stream()
 
+    # Launches of the timed step: one execute and one reduce per GEMM, or, with
+    # --group-levels, the GEMMs of a DAG level (independent, dispatched together,
+    # Sec. 4.1) that have the same shape and storage form (the Q, K, V
+    # projections; gate and up) as one grouped execute and one grouped reduce
+    # launch over a shared task list.  Uniform tilings only: c4 draws a
+    # different tiling per GEMM.
+    grouping = args.group_levels and args.config != "c4"
+    groups, open_group = [], {}
+    for i, (g, _, _, _) in enumerate(gemms):
+        key = (g.level, g.kind, g.M, g.N, g.K, g.transA, g.transB)
+        if grouping and key in open_group and len(open_group[key]) < 8:
+            open_group[key].append(i)
+        else:
+            open_group[key] = [i]
+            groups.append(open_group[key])
+    launches = []
+    level_used = {}
+    for members in groups:
+        g0 = gemms[members[0]][0]
+        if len(members) == 1:
+            plan = gemms[members[0]][1]
+        else:
+            plan = cleave.plan_batched(g0.M, g0.N, g0.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, len(members))
+            plan.upload()
+        off = level_used.get(g0.level, 0)
+        level_used[g0.level] = off + plan.partial_elems
+        launches.append({
+            "name": "+".join(gemms[i][0].name for i in members), "members": members, "plan": plan,
+            "A": [gemms[i][2] for i in members], "B": [gemms[i][3] for i in members],
+            "C": [outputs[i] for i in members], "slot": workspace[off:off + plan.partial_elems],
+            "transA": g0.transA, "transB": g0.transB,
+            "flops": sum(gemms[i][0].flops for i in members),
+            "reduce_bytes": sum(gemms[i][1].partial_elems * 4 + gemms[i][0].M * gemms[i][0].N * 4 for i in members),
+            "tasks": plan.num_tasks})
+
     def step(events=None):
         # one event between consecutive launches: the end of one kernel's
         # interval is the start of the next one's
         if events is not None:
             prev = torch.cuda.Event(enable_timing=True)
             prev.record(stream)
-        for i, (g, plan, dA, dB) in enumerate(gemms):
-            cleave.execute(plan, dA, dB, slots[i], g.transA, g.transB)
+        for i, L in enumerate(launches):
+            if len(L["members"]) == 1:
+                cleave.execute(L["plan"], L["A"][0], L["B"][0], L["slot"], L["transA"], L["transB"])
+            else:
+                cleave.execute_grouped(L["plan"], L["A"], L["B"], L["slot"], L["transA"], L["transB"])
             if events is not None:
                 mid = torch.cuda.Event(enable_timing=True)
                 mid.record(stream)
-            cleave.reduce(plan, slots[i], outputs[i])
+            if len(L["members"]) == 1:
+                cleave.reduce(L["plan"], L["slot"], L["C"][0])
+            else:
+                cleave.reduce_grouped(L["plan"], L["slot"], L["C"])
             if events is not None:
                 end = torch.cuda.Event(enable_timing=True)
                 end.record(stream)
@@ -164,20 +208,20 @@ def main():
     gpu_ms = t_begin.elapsed_time(t_end)
     ms_per_step = max(gpu_ms, wall * 1e3) / args.steps
 
-    exec_ms = [0.0] * len(gemms)
-    red_ms = [0.0] * len(gemms)
+    exec_ms = [0.0] * len(launches)
+    red_ms = [0.0] * len(launches)
     for i, e0, e1, e2 in events:
         exec_ms[i] += e0.elapsed_time(e1)
         red_ms[i] += e1.elapsed_time(e2)
     exec_ms = [x / args.steps for x in exec_ms]
     red_ms = [x / args.steps for x in red_ms]
     # each step on its own: first event of the step to its last
-    n_g = len(gemms)
+    n_g = len(launches)
     step_ms = sorted(events[k * n_g][1].elapsed_time(events[k * n_g + n_g - 1][3]) for k in range(args.steps))
     step_median = (step_ms[(len(step_ms) - 1) // 2] + step_ms[len(step_ms) // 2]) / 2
 
-    flops = [g.flops for g, _, _, _ in gemms]
-    red_bytes = [plan.partial_elems * 4 + g.M * g.N * 4 for g, plan, _, _ in gemms]
+    flops = [L["flops"] for L in launches]
+    red_bytes = [L["reduce_bytes"] for L in launches]
     total_flops = float(sum(flops))
     exec_total_ms = sum(exec_ms)
     red_total_ms = sum(red_ms)
@@ -185,15 +229,15 @@ def main():
     red_gbps = sum(red_bytes) / (red_total_ms * 1e-3) / 1e9
     value = total_flops / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
-    counters_valid = (args.config == COUNTER_TRAFFIC["workload"] and
+    counters_valid = (args.config == COUNTER_TRAFFIC["workload"] and not grouping and
                       kernel_sources_digest() == COUNTER_TRAFFIC["sources_sha256"])
     exec_traffic = round(COUNTER_TRAFFIC["execute_bytes_per_launch"]) if counters_valid else None
     red_traffic = round(COUNTER_TRAFFIC["reduce_bytes_per_launch"]) if counters_valid else None
 
-    per_gemm = [{"gemm": g.name, "tasks": plan.num_tasks, "kernel": plan.last_kernel,
-                 "execute_ms": round(exec_ms[i], 4), "execute_tflops": round(flops[i] / exec_ms[i] / 1e9, 1),
-                 "reduce_ms": round(red_ms[i], 4), "reduce_gbps": round(red_bytes[i] / red_ms[i] / 1e6, 1)}
-                for i, (g, plan, _, _) in enumerate(gemms)]
+    per_launch = [{"gemms": L["name"], "tasks": L["tasks"], "kernel": L["plan"].last_kernel,
+                   "execute_ms": round(exec_ms[i], 4), "execute_tflops": round(flops[i] / exec_ms[i] / 1e9, 1),
+                   "reduce_ms": round(red_ms[i], 4), "reduce_gbps": round(red_bytes[i] / red_ms[i] / 1e6, 1)}
+                  for i, L in enumerate(launches)]
 
     result = {
         "metric": "sub-GEMM task TFLOP/s (layer fwd+bwd, execute + reduce)",
@@ -209,8 +253,8 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {
-            "workload": ("%s: layer fwd+bwd, %d GEMMs, %d tasks, " % (
-                cfg.name, len(gemms), sum(p.num_tasks for _, p, _, _ in gemms))) + (
+            "workload": ("%s: layer fwd+bwd, %d GEMMs in %d launches, %d tasks, " % (
+                cfg.name, len(gemms), len(launches), sum(p.num_tasks for _, p, _, _ in gemms))) + (
                 "heterogeneous tiles (edges 128..1024), K-split 1..8 per tile" if args.config == "c4" else
                 "uniform %dx%d tiles, K-split %d" % (cfg.tile_m, cfg.tile_n, cfg.ksplit)),
             "tile": [cfg.tile_m, cfg.tile_n], "ksplit": cfg.ksplit, "seed": cfg.seed,
@@ -231,19 +275,19 @@ def main():
             "traffic_unit": "HBM-side bytes per launch (counters)",
             "algorithmic_bytes_per_launch_avg": sum(
                 (g.M * g.K + g.K * g.N) * in_bytes + plan.partial_elems * 4
-                for g, plan, _, _ in gemms) / len(gemms),
-            "launches_per_step": len(gemms),
-            "avg_launch_ms": round(exec_total_ms / len(gemms), 4),
-            "flops_per_launch_avg": total_flops / len(gemms),
+                for g, plan, _, _ in gemms) / len(launches),
+            "launches_per_step": len(launches),
+            "avg_launch_ms": round(exec_total_ms / len(launches), 4),
+            "flops_per_launch_avg": total_flops / len(launches),
         },
         "reduce_roofline": {
             "kernel": "reduce", "bound": "hbm",
             "achieved": round(red_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
             "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": red_traffic,
-            "avg_launch_ms": round(red_total_ms / len(gemms), 4),
-            "bytes_per_launch_avg": sum(red_bytes) / len(gemms),
+            "avg_launch_ms": round(red_total_ms / len(launches), 4),
+            "bytes_per_launch_avg": sum(red_bytes) / len(launches),
         },
-        "per_gemm": per_gemm,
+        "per_launch": per_launch,
         "paper_context": "paper reports cost-model times only (e.g. LLaMA-13B fwd GEMMs 0.063 s/step "
                          "at A100 peak rate, Table 2); no measured kernel numbers",
     }
@@ -266,7 +310,7 @@ def main():
         result["hip_graph"] = {"ms_per_step": round(graph_ms, 4),
                                "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 2),
                                "note": "the %d launches of a step captured once and replayed; `value` is the "
-                                       "eager figure" % (2 * len(gemms))}
+                                       "eager figure" % (2 * len(launches))}
         del graph
 
     # ---- returned-block check (outside the timed step; reported on its own) -
