@@ -254,11 +254,16 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   const cleave::WorkItem* d_lists[cleave::kNumTileClasses] = {plan->d_items[0], plan->d_items[1]};
   int64_t counts[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items[0].size()),
                                              static_cast<int64_t>(plan->items[1].size())};
+  // leading items of each list whose chunk is a whole number of direct-kernel K steps
+  int64_t whole_steps[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items_whole_steps[0]),
+                                                  static_cast<int64_t>(plan->items_whole_steps[1])};
   if (!task_ids && prefers_fine(plan->items[cleave::kTileLarge].size())) {
     d_lists[cleave::kTileLarge] = nullptr;
     counts[cleave::kTileLarge] = 0;
+    whole_steps[cleave::kTileLarge] = 0;
     d_lists[cleave::kTileSmall] = plan->d_items_fine;
     counts[cleave::kTileSmall] = static_cast<int64_t>(plan->items_fine.size());
+    whole_steps[cleave::kTileSmall] = static_cast<int64_t>(plan->items_fine_whole_steps);
   }
   if (task_ids) {
     // The subset tables live in a scratch buffer of the plan that a previous
@@ -278,6 +283,11 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     }
     int64_t pos = 0;
     for (int c = 0; c < cleave::kNumTileClasses; ++c) {
+      // same two parts as the plan's own lists, the caller's order kept inside each
+      const auto first_ragged = std::stable_partition(
+          subset[c].begin(), subset[c].end(),
+          [](const cleave::WorkItem& w) { return w.k_len % cleave::kDirectKStep == 0; });
+      whole_steps[c] = static_cast<int64_t>(first_ragged - subset[c].begin());
       counts[c] = static_cast<int64_t>(subset[c].size());
       d_lists[c] = plan->d_subset_items + pos;
       if (counts[c] > 0)
@@ -309,27 +319,35 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     args.C = asm_to.C;
     args.ldc = asm_to.ldc;
     args.c_bf16 = asm_to.out_dtype == CLEAVE_BF16 ? 1 : 0;
-    const bool direct = vec && dtype == CLEAVE_BF16 &&
-                        (cleave::direct_k_step() == 32 ? plan->all_klen_mult32 : plan->all_klen_mult64);
-    if (direct) {
+    // bf16 with 16-byte loads: items made of whole K steps go to the direct
+    // kernel, the others (if any) to the staged one.  Which kernel computes a
+    // block depends only on the block's own task record.
+    const int64_t n_direct = (vec && dtype == CLEAVE_BF16) ? whole_steps[c] : 0;
+    const int64_t n_staged = counts[c] - n_direct;
+    if (n_direct > 0) {
       // Persistent workgroups, as many as the chip holds at once: each walks
       // the item list with the grid as stride and fetches the head of its next
       // item while it stores the current one.
+      args.items = d_lists[c];
+      args.n_items = n_direct;
       const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(c);
-      const int grid = static_cast<int>(std::min<int64_t>(counts[c], resident));
+      const int grid = static_cast<int>(std::min<int64_t>(n_direct, resident));
       CLEAVE_HIP(cleave::launch_execute_direct(args, c, grid, stream));
-    } else {
+    }
+    if (n_staged > 0) {
       // One workgroup per work item (the kernel loops only if the grid is
       // capped): the hardware dispatcher then balances uneven items and keeps
       // the workgroups that share a CU out of phase.
+      args.items = d_lists[c] + n_direct;
+      args.n_items = n_staged;
       constexpr int64_t kMaxGrid = int64_t{1} << 20;
-      const int grid = static_cast<int>(std::min<int64_t>(counts[c], kMaxGrid));
+      const int grid = static_cast<int>(std::min<int64_t>(n_staged, kMaxGrid));
       CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
     }
     if (counts[c] > most) {
       most = counts[c];
-      plan->last_kernel = direct ? direct_kernel_name(c, transA, transB)
-                                 : kernel_name(dtype, c, vec, transA, transB);
+      plan->last_kernel = n_direct >= n_staged ? direct_kernel_name(c, transA, transB)
+                                               : kernel_name(dtype, c, vec, transA, transB);
     }
   }
   return CLEAVE_OK;

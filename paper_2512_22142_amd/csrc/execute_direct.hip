@@ -461,7 +461,8 @@ using LargeShape = CLEAVE_DIRECT_SHAPE_LARGE;
 using SmallShape = CLEAVE_DIRECT_SHAPE_SMALL;
 static_assert(LargeShape::TM == kLargeTileRows && LargeShape::TN == kLargeTileCols,
               "the kernel's tile must be the host's sub-tile of the large class");
-static_assert(LargeShape::BK == SmallShape::BK, "one K step for both classes");
+static_assert(LargeShape::BK == kDirectKStep && SmallShape::BK == kDirectKStep,
+              "the host sorts work items by whether their chunk is a multiple of this K step");
 
 template <typename S>
 hipError_t launch_layouts(const ExecuteArgs& args, int grid, hipStream_t stream) {
@@ -475,7 +476,6 @@ hipError_t launch_layouts(const ExecuteArgs& args, int grid, hipStream_t stream)
 
 }  // namespace
 
-int direct_k_step() { return LargeShape::BK; }
 
 int direct_workgroups_per_cu(int tile_class) {
   return tile_class == kTileLarge ? LargeShape::WGS : SmallShape::WGS;

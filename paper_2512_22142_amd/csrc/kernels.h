@@ -58,14 +58,12 @@ hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bo
                           hipStream_t stream);
 
 // Enqueues the bf16 direct-to-LDS execute kernel for one tile class.  The
-// caller has checked the 16-byte load conditions and that every chunk length
-// is a multiple of direct_k_step() elements.
+// caller has checked the 16-byte load conditions and that the chunk length of
+// every item is a multiple of kDirectKStep elements.
 hipError_t launch_execute_direct(const ExecuteArgs& args, int tile_class, int grid,
                                  hipStream_t stream);
 // Workgroups of the direct kernel that one CU holds at a time, per tile class.
 int direct_workgroups_per_cu(int tile_class);
-// Elements of K the direct kernel consumes per step: chunk lengths must be multiples of it.
-int direct_k_step();
 
 struct ReduceArgs {
   const cleave_task* tasks;

@@ -62,8 +62,18 @@ void order_work_items(cleave_plan* p) {
   }
   for (int list = 0; list < kNumTileClasses + 1; ++list) {
     const int cls = list < kNumTileClasses ? list : kTileSmall;
-    const std::vector<WorkItem>& source = list < kNumTileClasses ? all[cls] : fine[kTileSmall];
+    const std::vector<WorkItem>& whole_list = list < kNumTileClasses ? all[cls] : fine[kTileSmall];
     std::vector<WorkItem>& ordered = list < kNumTileClasses ? p->items[cls] : p->items_fine;
+    size_t& whole_steps = list < kNumTileClasses ? p->items_whole_steps[cls] : p->items_fine_whole_steps;
+    ordered.reserve(whole_list.size());
+    // Two parts, each ordered on its own: first the items the direct kernel
+    // can take (chunk = whole K steps), then the others.
+    for (int part = 0; part < 2; ++part) {
+    std::vector<WorkItem> source;
+    for (const WorkItem& w : whole_list)
+      if ((w.k_len % kDirectKStep == 0) == (part == 0)) source.push_back(w);
+    if (part == 0) whole_steps = source.size();
+    if (source.empty()) continue;
     const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
     const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
     struct Key {
@@ -76,7 +86,7 @@ void order_work_items(cleave_plan* p) {
     // the other.  Large members (the GEMMs of one DAG level) are spread over
     // the XCDs like a single GEMM, and the members take turns patch by patch,
     // so that an operand panel they share is still in L2 for the next one.
-    const bool member_per_xcd = p->batch > 0 && source.size() / static_cast<size_t>(p->batch) < kSpreadItems;
+    const bool member_per_xcd = p->batch > 0 && whole_list.size() / static_cast<size_t>(p->batch) < kSpreadItems;
     for (const WorkItem& w : source) {
       const cleave_task& t = p->tasks[w.task];
       const uint32_t m = w.m_base;
@@ -106,7 +116,6 @@ void order_work_items(cleave_plan* p) {
     // Interleave; when a region runs out, the slot is filled from the region
     // that has most left, so the list has no holes.
     size_t pos[kXcds] = {};
-    ordered.reserve(source.size());
     for (size_t i = 0; i < longest; ++i) {
       for (int x = 0; x < kXcds; ++x) {
         int src = x;
@@ -127,6 +136,7 @@ void order_work_items(cleave_plan* p) {
     }
     for (int x = 0; x < kXcds; ++x)
       for (; pos[x] < lists[x].size(); ++pos[x]) ordered.push_back(lists[x][pos[x]].item);
+    }
   }
 }
 
@@ -201,8 +211,6 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
       const uint32_t mn_or = t.m0 | t.m_len | t.n0 | t.n_len;
       p->all_k_mult8 &= (k_or % 8 == 0);
       p->all_k_mult4 &= (k_or % 4 == 0);
-      p->all_klen_mult32 &= (t.k_len % 32 == 0);
-      p->all_klen_mult64 &= (t.k_len % 64 == 0);
       p->all_mn_mult8 &= (mn_or % 8 == 0);
       p->all_mn_mult4 &= (mn_or % 4 == 0);
       p->all_n_mult4 &= ((t.n0 | t.n_len) % 4 == 0);

@@ -38,6 +38,10 @@ inline int tile_class_of(const cleave_task& t) {
 // block, computed over the task's whole chunk of the inner dimension.  The
 // record carries everything a workgroup needs, so that one load -- issued well
 // ahead -- replaces the dependent pair "which task, then that task's record".
+// Elements of K the direct (global -> LDS) execute kernel consumes per step: it
+// takes only items whose chunk length is a multiple of this.
+constexpr uint32_t kDirectKStep = 64;
+
 struct alignas(16) WorkItem {
   uint32_t m_base, n_base;    // first row / column of the sub-tile in the logical output
   uint32_t k0, k_len;         // the task's chunk
@@ -107,16 +111,19 @@ struct cleave_plan {
   int64_t batch = 0;         // > 0: a batch of that many M x N x K GEMMs, task.gemm_id = member
   bool all_k_mult8 = true;   // every k0 and k_len is a multiple of 8
   bool all_k_mult4 = true;
-  bool all_klen_mult32 = true;  // every k_len is a multiple of 32
-  bool all_klen_mult64 = true;
   bool all_mn_mult8 = true;  // every m0, m_len, n0, n_len is a multiple of 8
   bool all_mn_mult4 = true;
   bool all_n_mult4 = true;   // every n0, n_len multiple of 4 (vector path of reduce)
   std::vector<cleave_task> tasks;
-  std::vector<cleave::WorkItem> items[cleave::kNumTileClasses];  // all tasks, launch order
+  // All tasks, launch order.  Each list starts with the items whose chunk is a
+  // whole number of the direct kernel's K steps (items_whole_steps of them);
+  // the rest can only run in the staged kernel.
+  std::vector<cleave::WorkItem> items[cleave::kNumTileClasses];
+  size_t items_whole_steps[cleave::kNumTileClasses] = {0, 0};
   // All tasks cut into small-class sub-tiles only: used when the large class
   // would leave most of the CUs without a work item.
   std::vector<cleave::WorkItem> items_fine;
+  size_t items_fine_whole_steps = 0;
   std::vector<cleave::ReduceItem> reduce_items;
 
   // Device copies (current device at first use).

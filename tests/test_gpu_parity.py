@@ -116,6 +116,38 @@ def test_heterogeneous_plan_small():
     check_against_oracle(run, opA, opB, "bf16", tasks)
 
 
+def test_mixed_chunk_lengths_reissue_bitwise():
+    """Tiles whose chunks are whole K steps of the fast kernel next to tiles whose
+    chunks are not (K = 768: S = 1, 2, 4 give 768, 384, 192; S = 8 gives 96): a
+    block's bits depend on its own task record only, whichever other tasks run
+    in the same call and in whatever order they are listed."""
+    M, N, K = 768, 768, 768
+    band_h = [512, 256]
+    col_w = [[256, 512], [256, 256, 256]]
+    ks = [8, 1, 2, 8, 4]
+    a = make_matrix(73, M, K, "bf16")
+    b = make_matrix(74, K, N, "bf16", std=0.02)
+    plan = cleave.plan_explicit(M, N, K, band_h, col_w, ks)
+    tasks, _ = planner.plan_explicit(M, N, K, band_h, col_w, ks)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    run = GpuGemm(plan, a, b).run()
+    opA, opB = og.logical_operands(a, 0, b, 0)
+    check_against_oracle(run, opA, opB, "bf16", tasks)
+    first = run.partials_host().copy()
+    lost = [len(tasks) - 1, 0, 9, 8, 3, 12]            # both kinds, not in canonical order
+    assert {int(tasks[i]["k_len"]) % 64 for i in lost} == {0, 32}
+    poisoned = first.copy()
+    for i in lost:
+        block_of(poisoned, tasks[i])[:] = np.nan
+    run.partials.copy_(torch.from_numpy(poisoned).cuda())
+    run.execute(task_ids=lost)
+    assert run.partials_host().tobytes() == first.tobytes()
+    for i in (0, 8):                                     # one task alone
+        run.partials.fill_(float("nan"))
+        run.execute(task_ids=[i])
+        assert block_of(run.partials_host(), tasks[i]).tobytes() == block_of(first, tasks[i]).tobytes()
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_reissued_tasks_are_bitwise_identical(dtype):
     M, N, K = 768, 640, 512
