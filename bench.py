@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "11b5472c51c3019b13e72e065d70ff5514092795f45a5615506894f478cf8cb7",
-    "execute_bytes_per_launch": (2.0 * 243583 + 394338) * 1024,
+    "sources_sha256": "8042ac016fa4835c70a3e84a75c706a0a405a85659ef14d644547bf92375803e",
+    "execute_bytes_per_launch": (2.0 * 241436 + 394338) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194739 + 97134) * 1024,
 }
 
