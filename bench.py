@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "8042ac016fa4835c70a3e84a75c706a0a405a85659ef14d644547bf92375803e",
-    "execute_bytes_per_launch": (2.0 * 241436 + 394338) * 1024,
+    "sources_sha256": "9bfec9d12d2c4fcdefe59ac1a131b9ffd6400cb2e30989c91369ba6411c0cc8a",
+    "execute_bytes_per_launch": (2.0 * 241521 + 394338) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194739 + 97134) * 1024,
 }
 

@@ -461,8 +461,8 @@ using LargeShape = CLEAVE_DIRECT_SHAPE_LARGE;
 using SmallShape = CLEAVE_DIRECT_SHAPE_SMALL;
 static_assert(LargeShape::TM == kLargeTileRows && LargeShape::TN == kLargeTileCols,
               "the kernel's tile must be the host's sub-tile of the large class");
-static_assert(LargeShape::BK == kDirectKStep && SmallShape::BK == kDirectKStep,
-              "the host sorts work items by whether their chunk is a multiple of this K step");
+static_assert(kDirectKStep % LargeShape::BK == 0 && kDirectKStep % SmallShape::BK == 0,
+              "the host hands this kernel the work items whose chunk is a multiple of kDirectKStep");
 
 template <typename S>
 hipError_t launch_layouts(const ExecuteArgs& args, int grid, hipStream_t stream) {

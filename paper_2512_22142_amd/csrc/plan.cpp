@@ -346,11 +346,11 @@ extern "C" int cleave_plan_explicit(int64_t M, int64_t N, int64_t K, int32_t n_b
 }
 
 extern "C" int64_t cleave_plan_num_tasks(const cleave_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->tasks.size()) : CLEAVE_EINVAL;
+  return plan ? static_cast<int64_t>(plan->tasks.size()) : int64_t{CLEAVE_EINVAL};
 }
 
 extern "C" int64_t cleave_plan_num_tiles(const cleave_plan* plan) {
-  return plan ? plan->num_tiles : CLEAVE_EINVAL;
+  return plan ? plan->num_tiles : int64_t{CLEAVE_EINVAL};
 }
 
 extern "C" const cleave_task* cleave_plan_tasks(const cleave_plan* plan) {
@@ -358,7 +358,7 @@ extern "C" const cleave_task* cleave_plan_tasks(const cleave_plan* plan) {
 }
 
 extern "C" int64_t cleave_plan_partial_elems(const cleave_plan* plan) {
-  return plan ? plan->partial_elems : CLEAVE_EINVAL;
+  return plan ? plan->partial_elems : int64_t{CLEAVE_EINVAL};
 }
 
 extern "C" int cleave_plan_dims(const cleave_plan* plan, int64_t* dims) {
