@@ -142,7 +142,12 @@ void cleave_plan_destroy(cleave_plan* plan);
  * that start on 16-byte boundaries and inner chunks that are multiples of 16
  * bytes take the fast path, anything else a slower guarded path).
  * The bits of a task's block depend only on its record, the operands and
- * dtype/layout -- not on which other tasks run in the same call. */
+ * dtype/layout -- not on which other tasks run in the same call.
+ * A call with task_ids builds the work list of that subset on the host and
+ * copies it into a device table the plan owns (grown on demand): it waits on
+ * the host for work enqueued earlier on hip_stream that may still read that
+ * table, and for its own copy, before it enqueues the kernels.  A call without
+ * task_ids neither waits nor allocates. */
 int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
                    const void* A, int64_t lda, int transA,
                    const void* B, int64_t ldb, int transB,
