@@ -40,8 +40,10 @@
  *   - execute and reduce enqueue work on the given HIP stream (a hipStream_t
  *     passed as void*, NULL = the default stream) and return without waiting
  *     for it.  The first execute/reduce of a plan on a device uploads the
- *     plan's tables with a blocking copy; cleave_plan_upload does that ahead
- *     of time.
+ *     plan's tables with a blocking copy and allocates everything later calls
+ *     need (including the work-list memory of subset launches);
+ *     cleave_plan_upload does that ahead of time.  After it, execute and
+ *     reduce allocate nothing.
  */
 #ifndef CLEAVE_H
 #define CLEAVE_H
@@ -143,11 +145,24 @@ void cleave_plan_destroy(cleave_plan* plan);
  * bytes take the fast path, anything else a slower guarded path).
  * The bits of a task's block depend only on its record, the operands and
  * dtype/layout -- not on which other tasks run in the same call.
- * A call with task_ids builds the work list of that subset on the host and
- * copies it into a device table the plan owns (grown on demand): it waits on
- * the host for work enqueued earlier on hip_stream that may still read that
- * table, and for its own copy, before it enqueues the kernels.  A call without
- * task_ids neither waits nor allocates. */
+ * A call with task_ids is stream-ordered like any other: the task indices
+ * travel in kernel arguments, the subset's work list is written on the device
+ * into memory the plan set aside when its tables were uploaded, and nothing
+ * is allocated, copied or waited for on the host.  Such calls may be issued
+ * on several streams and from several threads at once (the plan serialises
+ * its own bookkeeping) and may be captured into a HIP graph:
+ *   - outside capture, a call reuses work-list memory of an earlier subset
+ *     call of the same plan only after that call's kernels have finished; the
+ *     host waits only in the corner case that more than two full task lists'
+ *     worth of subset work of one plan is still in flight;
+ *   - under stream capture, the call's work-list memory stays reserved until
+ *     the plan is destroyed (the graph may be replayed at any time); the
+ *     memory set aside for captured calls holds one full task list's worth of
+ *     work items (every task listed once, over all captured calls of the
+ *     plan, always fits), beyond that CLEAVE_ENOMEM.  The plan's tables must
+ *     have been uploaded before capture begins (cleave_plan_upload or any
+ *     earlier call).
+ */
 int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
                    const void* A, int64_t lda, int transA,
                    const void* B, int64_t ldb, int transB,

@@ -15,6 +15,10 @@ include/cleave.h); build it with `python -m paper_2512_22142_amd.build`.
 _BINDING_NAMES = (
     "BF16",
     "F32",
+    "OK",
+    "EINVAL",
+    "ENOMEM",
+    "EHIP",
     "CleaveError",
     "Device",
     "Plan",

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcleave.so")
 
-SOURCES = ["plan.cpp", "scheduler.cpp", "api.cpp", "execute.hip", "execute_direct.hip", "reduce.hip", "verify.hip"]
+SOURCES = ["plan.cpp", "scheduler.cpp", "api.cpp", "execute.hip", "execute_direct.hip", "reduce.hip", "verify.hip", "subset.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = [

@@ -6,6 +6,7 @@
 #include <cstdint>
 #include <limits>
 #include <map>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -42,20 +43,29 @@ void free_verify_device(cleave::VerifyTables* v) {
   v->d_proj = v->d_item_sums = nullptr;
 }
 
+void free_subset_ring(cleave::SubsetRing* r) {
+  if (r->d_ring) (void)hipFree(r->d_ring);
+  if (r->d_captured) (void)hipFree(r->d_captured);
+  for (const auto& f : r->in_flight) (void)hipEventDestroy(f.done);
+  for (hipEvent_t e : r->idle_events) (void)hipEventDestroy(e);
+  r->d_ring = r->d_captured = nullptr;
+  r->in_flight.clear();
+  r->idle_events.clear();
+  r->max_items = r->pos = r->captured_used = 0;
+}
+
 void free_device_tables(cleave_plan* p) {
   free_verify_device(p->verify);
   if (p->d_tasks) (void)hipFree(p->d_tasks);
   for (int c = 0; c < cleave::kNumTileClasses; ++c)
     if (p->d_items[c]) (void)hipFree(p->d_items[c]);
   if (p->d_reduce_items) (void)hipFree(p->d_reduce_items);
-  if (p->d_subset_items) (void)hipFree(p->d_subset_items);
+  free_subset_ring(&p->subset);
   p->d_tasks = nullptr;
   if (p->d_items_fine) (void)hipFree(p->d_items_fine);
   p->d_items_fine = nullptr;
   p->d_items[0] = p->d_items[1] = nullptr;
   p->d_reduce_items = nullptr;
-  p->d_subset_items = nullptr;
-  p->d_subset_capacity = 0;
   p->device = -1;
 }
 
@@ -70,16 +80,64 @@ int upload_vector(const std::vector<T>& v, T** dst) {
   return CLEAVE_OK;
 }
 
+// Once per device and process: the execute kernels' dynamic-LDS limits and the
+// CU count.  Done when a plan's tables are uploaded, so that no launch has to.
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mu;
+int g_device_cus[kMaxDevices] = {};   // 0 = not initialised
+
+int ensure_device_ready(int dev, int* cus) {
+  if (dev < 0 || dev >= kMaxDevices) return CLEAVE_EINVAL;
+  std::lock_guard<std::mutex> lock(g_device_mu);
+  if (g_device_cus[dev] == 0) {
+    CLEAVE_HIP(cleave::configure_execute_kernels());
+    CLEAVE_HIP(cleave::configure_execute_direct_kernels());
+    int n = 0;
+    CLEAVE_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+    g_device_cus[dev] = std::max(n, 1);
+  }
+  if (cus) *cus = g_device_cus[dev];
+  return CLEAVE_OK;
+}
+
+constexpr int kSubsetEvents = 16;
+
+int allocate_subset_ring(cleave_plan* p) {
+  cleave::SubsetRing& r = p->subset;
+  r.max_items = static_cast<int64_t>(std::max(p->items[0].size() + p->items[1].size(), p->items_fine.size()));
+  if (r.max_items == 0) return CLEAVE_OK;
+  const size_t item_bytes = static_cast<size_t>(r.max_items) * sizeof(cleave::WorkItem);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&r.d_ring), 2 * item_bytes);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&r.d_captured), item_bytes);
+  if (e == hipErrorOutOfMemory) return CLEAVE_ENOMEM;
+  if (e != hipSuccess) return hip_fail(e);
+  try {
+    r.idle_events.reserve(kSubsetEvents);
+    r.in_flight.reserve(kSubsetEvents);
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  for (int i = 0; i < kSubsetEvents; ++i) {
+    hipEvent_t ev = nullptr;
+    CLEAVE_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    r.idle_events.push_back(ev);
+  }
+  return CLEAVE_OK;
+}
+
 int ensure_uploaded(cleave_plan* p) {
   int dev = 0;
   CLEAVE_HIP(hipGetDevice(&dev));
   if (p->device == dev) return CLEAVE_OK;
   if (p->device >= 0) free_device_tables(p);
-  int rc = upload_vector(p->tasks, &p->d_tasks);
+  int rc = ensure_device_ready(dev, nullptr);
+  if (rc != CLEAVE_OK) return rc;
+  rc = upload_vector(p->tasks, &p->d_tasks);
   for (int c = 0; rc == CLEAVE_OK && c < cleave::kNumTileClasses; ++c)
     rc = upload_vector(p->items[c], &p->d_items[c]);
   if (rc == CLEAVE_OK) rc = upload_vector(p->items_fine, &p->d_items_fine);
   if (rc == CLEAVE_OK) rc = upload_vector(p->reduce_items, &p->d_reduce_items);
+  if (rc == CLEAVE_OK) rc = allocate_subset_ring(p);
   if (rc != CLEAVE_OK) {
     free_device_tables(p);
     return rc;
@@ -89,14 +147,67 @@ int ensure_uploaded(cleave_plan* p) {
 }
 
 int compute_units(int* out) {
-  static thread_local int cached_dev = -1, cached_cus = 0;
   int dev = 0;
   CLEAVE_HIP(hipGetDevice(&dev));
-  if (dev != cached_dev) {
-    CLEAVE_HIP(hipDeviceGetAttribute(&cached_cus, hipDeviceAttributeMultiprocessorCount, dev));
-    cached_dev = dev;
+  return ensure_device_ready(dev, out);
+}
+
+// A slice of `total` work items for a subset launch on `stream`.  Eager
+// launches take the next slice of the ring (waiting, on the host, only for
+// earlier launches that still read the slice: none unless the ring has
+// wrapped onto unfinished work); launches under stream capture take a slice
+// of the second buffer that is never handed out again.  No allocation.
+int acquire_subset_slice(cleave::SubsetRing& r, int64_t total, bool capturing, cleave::WorkItem** out,
+                         int64_t* begin) {
+  if (total > r.max_items) return CLEAVE_EINVAL;   // cannot happen for distinct task ids
+  if (capturing) {
+    if (r.captured_used + total > r.max_items) return CLEAVE_ENOMEM;
+    *out = r.d_captured + r.captured_used;
+    *begin = -1;
+    r.captured_used += total;
+    return CLEAVE_OK;
   }
-  *out = std::max(cached_cus, 1);
+  if (r.pos + total > 2 * r.max_items) r.pos = 0;
+  const int64_t b = r.pos, e = r.pos + total;
+  // launches retire in order per stream, not across streams: check every record
+  for (size_t i = 0; i < r.in_flight.size();) {
+    const auto f = r.in_flight[i];
+    const bool overlaps = f.begin < e && b < f.end;
+    hipError_t q = overlaps ? hipEventSynchronize(f.done) : hipEventQuery(f.done);
+    if (q == hipSuccess) {
+      r.idle_events.push_back(f.done);
+      r.in_flight.erase(r.in_flight.begin() + static_cast<std::ptrdiff_t>(i));
+    } else if (q == hipErrorNotReady) {
+      ++i;
+    } else {
+      return hip_fail(q);
+    }
+  }
+  *out = r.d_ring + b;
+  *begin = b;
+  r.pos = e;
+  return CLEAVE_OK;
+}
+
+// Marks the slice [begin, begin + total) as read by what has been enqueued on
+// `stream` so far.
+int release_subset_slice(cleave::SubsetRing& r, int64_t begin, int64_t total, hipStream_t stream) {
+  if (begin < 0) return CLEAVE_OK;   // captured: never reused
+  if (r.idle_events.empty()) {
+    // every event is attached to a launch still in flight: wait for the oldest
+    const auto f = r.in_flight.front();
+    CLEAVE_HIP(hipEventSynchronize(f.done));
+    r.in_flight.erase(r.in_flight.begin());
+    r.idle_events.push_back(f.done);
+  }
+  hipEvent_t ev = r.idle_events.back();
+  r.idle_events.pop_back();
+  const hipError_t e = hipEventRecord(ev, stream);
+  if (e != hipSuccess) {
+    r.idle_events.push_back(ev);
+    return hip_fail(e);
+  }
+  r.in_flight.push_back({begin, begin + total, ev});
   return CLEAVE_OK;
 }
 
@@ -192,6 +303,23 @@ struct AssembleTarget {
   int out_dtype = CLEAVE_F32;
 };
 
+// Enqueues the kernels that write the work items of `entries` to `out`.
+int expand_subset(const cleave_task* d_tasks, const std::vector<cleave::SubsetEntry>& entries, bool fine,
+                  cleave::WorkItem* out, hipStream_t stream) {
+  cleave::ExpandArgs ea{};
+  ea.tasks = d_tasks;
+  ea.out = out;
+  ea.fine = fine ? 1u : 0u;
+  for (size_t first = 0; first < entries.size(); first += cleave::kSubsetEntriesPerLaunch) {
+    const size_t n = std::min<size_t>(cleave::kSubsetEntriesPerLaunch, entries.size() - first);
+    ea.n_entries = static_cast<uint32_t>(n);
+    std::copy(entries.begin() + static_cast<std::ptrdiff_t>(first),
+              entries.begin() + static_cast<std::ptrdiff_t>(first + n), ea.entries);
+    CLEAVE_HIP(cleave::launch_expand_subset(ea, stream));
+  }
+  return CLEAVE_OK;
+}
+
 int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, const void* A,
                  int64_t lda, int transA, const void* B, int64_t ldb, int transB, int dtype,
                  float* partials, const BatchLayout& bl, void* hip_stream,
@@ -216,22 +344,45 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     return large_items > 0 && large_items <= static_cast<size_t>(cus) / 2;
   };
 
-  // Work items of a subset, in the order the caller listed the tasks.
-  std::vector<cleave::WorkItem> subset[cleave::kNumTileClasses];
+  // Subset: where each listed task's work items go.  One list per tile class,
+  // each in two parts -- first the tasks whose chunk is a whole number of the
+  // direct kernel's K steps, then the others -- with the caller's order kept
+  // inside each part (the layout of the plan's own lists).
+  std::vector<cleave::SubsetEntry> entries;
+  int64_t sub_counts[cleave::kNumTileClasses][2] = {};
+  bool fine = false;
   if (task_ids) {
     try {
       std::vector<bool> seen(plan->tasks.size(), false);
+      size_t large_items = 0;
       for (int64_t i = 0; i < n_ids; ++i) {
         const int64_t id = task_ids[i];
         if (id < 0 || id >= static_cast<int64_t>(plan->tasks.size()) || seen[id]) return CLEAVE_EINVAL;
         seen[id] = true;
-        cleave::append_work_items(plan->tasks[id], static_cast<uint32_t>(id), subset);
+        const cleave::SubTiling st = cleave::sub_tiling(plan->tasks[id], false);
+        if (st.cls == cleave::kTileLarge) large_items += st.count();
       }
-      if (prefers_fine(subset[cleave::kTileLarge].size())) {
-        subset[0].clear();
-        subset[1].clear();
-        for (int64_t i = 0; i < n_ids; ++i)
-          cleave::append_work_items(plan->tasks[task_ids[i]], static_cast<uint32_t>(task_ids[i]), subset, true);
+      fine = prefers_fine(large_items);
+      const auto part_of = [](const cleave_task& t) { return t.k_len % cleave::kDirectKStep == 0 ? 0 : 1; };
+      for (int64_t i = 0; i < n_ids; ++i) {
+        const cleave_task& t = plan->tasks[task_ids[i]];
+        const cleave::SubTiling st = cleave::sub_tiling(t, fine);
+        sub_counts[st.cls][part_of(t)] += st.count();
+      }
+      int64_t next[cleave::kNumTileClasses][2];
+      int64_t pos = 0;
+      for (int c = 0; c < cleave::kNumTileClasses; ++c)
+        for (int part = 0; part < 2; ++part) {
+          next[c][part] = pos;
+          pos += sub_counts[c][part];
+        }
+      entries.reserve(static_cast<size_t>(n_ids));
+      for (int64_t i = 0; i < n_ids; ++i) {
+        const cleave_task& t = plan->tasks[task_ids[i]];
+        const cleave::SubTiling st = cleave::sub_tiling(t, fine);
+        int64_t& at = next[st.cls][part_of(t)];
+        entries.push_back({static_cast<uint32_t>(task_ids[i]), static_cast<uint32_t>(at)});
+        at += st.count();
       }
     } catch (const std::bad_alloc&) {
       return CLEAVE_ENOMEM;
@@ -265,40 +416,39 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     counts[cleave::kTileSmall] = static_cast<int64_t>(plan->items_fine.size());
     whole_steps[cleave::kTileSmall] = static_cast<int64_t>(plan->items_fine_whole_steps);
   }
+  // Subset launches: the work-item lists are written on the device, from the
+  // task records, into a slice of memory the plan set aside when its tables
+  // were uploaded -- stream-ordered, no host wait, no copy, no allocation.
+  std::unique_lock<std::mutex> subset_lock;
+  int64_t slice_begin = -1, slice_total = 0;
   if (task_ids) {
-    // The subset tables live in a scratch buffer of the plan that a previous
-    // subset launch on this stream may still be reading: wait, refill, and
-    // wait for the copy so that the host vectors can go away.
-    const int64_t total = static_cast<int64_t>(subset[0].size() + subset[1].size());
-    CLEAVE_HIP(hipStreamSynchronize(stream));
-    if (total > plan->d_subset_capacity) {
-      if (plan->d_subset_items) (void)hipFree(plan->d_subset_items);
-      plan->d_subset_items = nullptr;
-      plan->d_subset_capacity = 0;
-      hipError_t he = hipMalloc(reinterpret_cast<void**>(&plan->d_subset_items),
-                                static_cast<size_t>(total) * sizeof(cleave::WorkItem));
-      if (he == hipErrorOutOfMemory) return CLEAVE_ENOMEM;
-      if (he != hipSuccess) return hip_fail(he);
-      plan->d_subset_capacity = total;
+    subset_lock = std::unique_lock<std::mutex>(plan->subset.mu);
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    CLEAVE_HIP(hipStreamIsCapturing(stream, &capture));
+    for (int c = 0; c < cleave::kNumTileClasses; ++c) slice_total += sub_counts[c][0] + sub_counts[c][1];
+    cleave::WorkItem* slice = nullptr;
+    rc = acquire_subset_slice(plan->subset, slice_total, capture != hipStreamCaptureStatusNone, &slice,
+                              &slice_begin);
+    if (rc != CLEAVE_OK) return rc;
+    rc = expand_subset(plan->d_tasks, entries, fine, slice, stream);
+    if (rc != CLEAVE_OK) {
+      (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
+      return rc;
     }
     int64_t pos = 0;
     for (int c = 0; c < cleave::kNumTileClasses; ++c) {
-      // same two parts as the plan's own lists, the caller's order kept inside each
-      const auto first_ragged = std::stable_partition(
-          subset[c].begin(), subset[c].end(),
-          [](const cleave::WorkItem& w) { return w.k_len % cleave::kDirectKStep == 0; });
-      whole_steps[c] = static_cast<int64_t>(first_ragged - subset[c].begin());
-      counts[c] = static_cast<int64_t>(subset[c].size());
-      d_lists[c] = plan->d_subset_items + pos;
-      if (counts[c] > 0)
-        CLEAVE_HIP(hipMemcpyAsync(plan->d_subset_items + pos, subset[c].data(),
-                                  static_cast<size_t>(counts[c]) * sizeof(cleave::WorkItem),
-                                  hipMemcpyHostToDevice, stream));
+      d_lists[c] = slice + pos;
+      whole_steps[c] = sub_counts[c][0];
+      counts[c] = sub_counts[c][0] + sub_counts[c][1];
       pos += counts[c];
     }
-    CLEAVE_HIP(hipStreamSynchronize(stream));
   }
 
+  // whatever has been enqueued reads the slice: mark it even if a later launch fails
+  const auto launch_failed = [&](hipError_t e) {
+    if (task_ids) (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
+    return hip_fail(e);
+  };
   int64_t most = -1;
   for (int c = 0; c < cleave::kNumTileClasses; ++c) {
     if (counts[c] == 0) continue;
@@ -332,7 +482,8 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
       args.n_items = n_direct;
       const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(c);
       const int grid = static_cast<int>(std::min<int64_t>(n_direct, resident));
-      CLEAVE_HIP(cleave::launch_execute_direct(args, c, grid, stream));
+      const hipError_t he = cleave::launch_execute_direct(args, c, grid, stream);
+      if (he != hipSuccess) return launch_failed(he);
     }
     if (n_staged > 0) {
       // One workgroup per work item (the kernel loops only if the grid is
@@ -342,7 +493,8 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
       args.n_items = n_staged;
       constexpr int64_t kMaxGrid = int64_t{1} << 20;
       const int grid = static_cast<int>(std::min<int64_t>(n_staged, kMaxGrid));
-      CLEAVE_HIP(cleave::launch_execute(args, dtype, c, vec, grid, stream));
+      const hipError_t he = cleave::launch_execute(args, dtype, c, vec, grid, stream);
+      if (he != hipSuccess) return launch_failed(he);
     }
     if (counts[c] > most) {
       most = counts[c];
@@ -350,6 +502,7 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
                                                : kernel_name(dtype, c, vec, transA, transB);
     }
   }
+  if (task_ids) return release_subset_slice(plan->subset, slice_begin, slice_total, stream);
   return CLEAVE_OK;
 }
 

@@ -349,19 +349,26 @@ __global__ __launch_bounds__(WM* WN * 64, (WM * WN > 4 ? 1 : 2)) void execute_ke
 template <int EB, int TM, int TN, int WM, int WN, int MODE_A, int MODE_B>
 hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
   constexpr size_t lds = (TM + TN) * kRowStride;
-  auto kern = execute_kernel<EB, TM, TN, WM, WN, MODE_A, MODE_B>;
-  static thread_local int configured_device = -1;
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (configured_device != dev) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (e != hipSuccess) return e;
-    configured_device = dev;
-  }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, stream, args);
+  hipLaunchKernelGGL((execute_kernel<EB, TM, TN, WM, WN, MODE_A, MODE_B>), dim3(grid),
+                     dim3(WM * WN * 64), lds, stream, args);
   return hipGetLastError();
+}
+
+template <int EB, int TM, int TN, int WM, int WN, int MODE_A, int MODE_B>
+hipError_t configure_one() {
+  return hipFuncSetAttribute(
+      reinterpret_cast<const void*>(execute_kernel<EB, TM, TN, WM, WN, MODE_A, MODE_B>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>((TM + TN) * kRowStride));
+}
+
+template <int EB, int TM, int TN, int WM, int WN>
+hipError_t configure_modes() {
+  hipError_t e = configure_one<EB, TM, TN, WM, WN, kScalar, kScalar>();
+  if (e == hipSuccess) e = configure_one<EB, TM, TN, WM, WN, kVecKContig, kVecKContig>();
+  if (e == hipSuccess) e = configure_one<EB, TM, TN, WM, WN, kVecKContig, kVecTransposed>();
+  if (e == hipSuccess) e = configure_one<EB, TM, TN, WM, WN, kVecTransposed, kVecKContig>();
+  if (e == hipSuccess) e = configure_one<EB, TM, TN, WM, WN, kVecTransposed, kVecTransposed>();
+  return e;
 }
 
 template <int EB, int TM, int TN, int WM, int WN>
@@ -376,6 +383,14 @@ hipError_t launch_modes(const ExecuteArgs& args, bool vec, int grid, hipStream_t
 }
 
 }  // namespace
+
+hipError_t configure_execute_kernels() {
+  hipError_t e = configure_modes<2, kLargeTileRows, kLargeTileCols, 2, kLargeTileCols / 64>();
+  if (e == hipSuccess) e = configure_modes<2, 128, 128, 2, 2>();
+  if (e == hipSuccess) e = configure_modes<4, kLargeTileRows, kLargeTileCols, 2, kLargeTileCols / 64>();
+  if (e == hipSuccess) e = configure_modes<4, 128, 128, 2, 2>();
+  return e;
+}
 
 hipError_t launch_execute(const ExecuteArgs& args, int dtype, int tile_class, bool vec, int grid,
                           hipStream_t stream) {

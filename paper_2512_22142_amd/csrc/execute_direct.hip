@@ -124,6 +124,11 @@ struct DirectTile {
   // for every load in flight before each LDS transpose read.  The statement
   // has no register outputs, so nothing the compiler may spill or reuse is
   // written asynchronously; completion is awaited with CLEAVE_WAIT_BARRIER.
+  // M0 is on the clobber list so that the compiler keeps no value of its own
+  // in M0 across the statement (it is a reserved register, hence the
+  // diagnostic silenced here; nothing needs it preserved).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
   __device__ __forceinline__ void issue(const unsigned char* gbase, uint32_t lds_tile,
                                         int wave) const {
 #pragma unroll
@@ -132,9 +137,10 @@ struct DirectTile {
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(lds), "v"(goff[i]), "s"(gbase)
-                   : "memory");
+                   : "memory", "m0");
     }
   }
+#pragma clang diagnostic pop
 };
 
 template <typename S, bool A_K, bool B_K>
@@ -432,19 +438,24 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 template <typename S, bool A_K, bool B_K>
 hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
   constexpr size_t lds = S::STAGES * S::kStage;
-  auto kern = execute_direct_kernel<S, A_K, B_K>;
-  static thread_local int configured_device = -1;
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (configured_device != dev) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (e != hipSuccess) return e;
-    configured_device = dev;
-  }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(S::NT), lds, stream, args);
+  hipLaunchKernelGGL((execute_direct_kernel<S, A_K, B_K>), dim3(grid), dim3(S::NT), lds, stream, args);
   return hipGetLastError();
+}
+
+template <typename S, bool A_K, bool B_K>
+hipError_t configure_one() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(execute_direct_kernel<S, A_K, B_K>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                             static_cast<int>(S::STAGES * S::kStage));
+}
+
+template <typename S>
+hipError_t configure_layouts() {
+  hipError_t e = configure_one<S, true, true>();
+  if (e == hipSuccess) e = configure_one<S, true, false>();
+  if (e == hipSuccess) e = configure_one<S, false, true>();
+  if (e == hipSuccess) e = configure_one<S, false, false>();
+  return e;
 }
 
 // Large class: 256 x 256 tile, 8 waves (2 x 4, each 128 x 64), 64 elements of
@@ -476,6 +487,11 @@ hipError_t launch_layouts(const ExecuteArgs& args, int grid, hipStream_t stream)
 
 }  // namespace
 
+
+hipError_t configure_execute_direct_kernels() {
+  const hipError_t e = configure_layouts<LargeShape>();
+  return e != hipSuccess ? e : configure_layouts<SmallShape>();
+}
 
 int direct_workgroups_per_cu(int tile_class) {
   return tile_class == kTileLarge ? LargeShape::WGS : SmallShape::WGS;

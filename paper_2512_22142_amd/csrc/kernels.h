@@ -65,6 +65,31 @@ hipError_t launch_execute_direct(const ExecuteArgs& args, int tile_class, int gr
 // Workgroups of the direct kernel that one CU holds at a time, per tile class.
 int direct_workgroups_per_cu(int tile_class);
 
+// Raises the dynamic-LDS limit of every execute kernel on the current device
+// (needed once per device and process, before the first launch).
+hipError_t configure_execute_kernels();
+hipError_t configure_execute_direct_kernels();
+
+// ---- work-item lists of subset launches ---------------------------------------
+// One entry per re-issued task: which task, and where its work items go.  The
+// entries travel in the kernel arguments, so the launch needs no host buffer,
+// no copy and nothing the caller could not capture into a HIP graph.
+struct SubsetEntry {
+  uint32_t task;   // index into the task table
+  uint32_t dst;    // index of the task's first work item in `out`
+};
+constexpr int kSubsetEntriesPerLaunch = 480;
+struct ExpandArgs {
+  const cleave_task* tasks;
+  WorkItem* out;
+  uint32_t n_entries;
+  uint32_t fine;             // every block cut into small-class sub-tiles
+  SubsetEntry entries[kSubsetEntriesPerLaunch];
+};
+static_assert(sizeof(ExpandArgs) <= 4096, "kernel arguments stay within 4 KB");
+// out[dst + sub] = work item `sub` of entries[e].task, for every entry.
+hipError_t launch_expand_subset(const ExpandArgs& args, hipStream_t stream);
+
 struct ReduceArgs {
   const cleave_task* tasks;
   const ReduceItem* items;

@@ -249,27 +249,9 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
 
 void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out,
                        bool fine) {
-  const int cls = fine ? static_cast<int>(kTileSmall) : tile_class_of(t);
-  const uint32_t tr = static_cast<uint32_t>(tile_rows(cls));
-  const uint32_t tc = static_cast<uint32_t>(tile_cols(cls));
-  const uint32_t sm = (t.m_len + tr - 1) / tr;
-  const uint32_t sn = (t.n_len + tc - 1) / tc;
-  for (uint32_t i = 0; i < sm; ++i)
-    for (uint32_t j = 0; j < sn; ++j) {
-      WorkItem w{};
-      w.m_base = t.m0 + i * tr;
-      w.n_base = t.n0 + j * tc;
-      w.k0 = t.k0;
-      w.k_len = t.k_len;
-      w.m_valid = std::min(tr, t.m_len - i * tr);
-      w.n_valid = std::min(tc, t.n_len - j * tc);
-      w.out_ld = t.n_len;
-      w.gemm_id = t.gemm_id;
-      w.out_off = t.partial_off + static_cast<uint64_t>(i) * tr * t.n_len + static_cast<uint64_t>(j) * tc;
-      w.task = task_index;
-      w.sub = i * sn + j;
-      out[cls].push_back(w);
-    }
+  const SubTiling s = sub_tiling(t, fine);
+  for (uint32_t sub = 0; sub < s.count(); ++sub)
+    out[s.cls].push_back(make_work_item(t, task_index, s, sub));
 }
 
 }  // namespace cleave

@@ -2,7 +2,10 @@
 // from it, and their lazily created device copies.
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "cleave.h"
@@ -25,12 +28,12 @@ constexpr int kLargeTileCols = CLEAVE_LARGE_TILE_COLS;
 constexpr int kSmallTileRows = 128;
 constexpr int kSmallTileCols = 128;
 
-inline int tile_rows(int cls) { return cls == kTileLarge ? kLargeTileRows : kSmallTileRows; }
-inline int tile_cols(int cls) { return cls == kTileLarge ? kLargeTileCols : kSmallTileCols; }
+__host__ __device__ inline int tile_rows(int cls) { return cls == kTileLarge ? kLargeTileRows : kSmallTileRows; }
+__host__ __device__ inline int tile_cols(int cls) { return cls == kTileLarge ? kLargeTileCols : kSmallTileCols; }
 
 // Blocks with both edges above 128 are cut into large sub-tiles, everything
 // else into 128 x 128 ones.
-inline int tile_class_of(const cleave_task& t) {
+__host__ __device__ inline int tile_class_of(const cleave_task& t) {
   return (t.m_len > 128 && t.n_len > 128) ? kTileLarge : kTileSmall;
 }
 
@@ -53,6 +56,43 @@ struct alignas(16) WorkItem {
   uint32_t sub;               // sub-tile index within the task's block, row-major
 };
 static_assert(sizeof(WorkItem) == 48, "WorkItem is 48 bytes");
+
+// How a task's block is cut into sub-tiles: the class (or, with `fine`, the
+// small class for every block) fixes the sub-tile, the block's extent the grid
+// of sub-tiles.  Host and device share this one definition.
+struct SubTiling {
+  int cls;
+  uint32_t tr, tc;    // sub-tile rows / columns
+  uint32_t sm, sn;    // grid of sub-tiles
+  __host__ __device__ uint32_t count() const { return sm * sn; }
+};
+__host__ __device__ inline SubTiling sub_tiling(const cleave_task& t, bool fine) {
+  SubTiling s;
+  s.cls = fine ? static_cast<int>(kTileSmall) : tile_class_of(t);
+  s.tr = static_cast<uint32_t>(tile_rows(s.cls));
+  s.tc = static_cast<uint32_t>(tile_cols(s.cls));
+  s.sm = (t.m_len + s.tr - 1) / s.tr;
+  s.sn = (t.n_len + s.tc - 1) / s.tc;
+  return s;
+}
+// Work item of sub-tile `sub` (row-major in the grid) of task record t.
+__host__ __device__ inline WorkItem make_work_item(const cleave_task& t, uint32_t task_index,
+                                                   const SubTiling& s, uint32_t sub) {
+  const uint32_t i = sub / s.sn, j = sub - i * s.sn;
+  WorkItem w{};
+  w.m_base = t.m0 + i * s.tr;
+  w.n_base = t.n0 + j * s.tc;
+  w.k0 = t.k0;
+  w.k_len = t.k_len;
+  w.m_valid = s.tr < t.m_len - i * s.tr ? s.tr : t.m_len - i * s.tr;
+  w.n_valid = s.tc < t.n_len - j * s.tc ? s.tc : t.n_len - j * s.tc;
+  w.out_ld = t.n_len;
+  w.gemm_id = t.gemm_id;
+  w.out_off = t.partial_off + static_cast<uint64_t>(i) * s.tr * t.n_len + static_cast<uint64_t>(j) * s.tc;
+  w.task = task_index;
+  w.sub = sub;
+  return w;
+}
 
 // One unit of work of the reduce kernel: a run of rows of one output tile.
 struct ReduceItem {
@@ -95,6 +135,32 @@ struct VerifyTables {
   double* d_item_sums = nullptr;  // one per item
 };
 
+// Device memory the subset launches of a plan put their work-item lists in.
+// Sized when the plan's tables are uploaded; nothing is allocated later.
+//   eager calls:    slices of a ring of 2 * max_items items; a slice is reused
+//                   only after the launch that read it has finished (one event
+//                   per launch; the host waits only if the ring has wrapped
+//                   onto a launch that is still running);
+//   captured calls: (the stream is being captured into a HIP graph) slices of a
+//                   second buffer of max_items items that are never reused,
+//                   since a graph may be replayed as long as the plan lives.
+// max_items = the plan's own work-item count under its finest cut, which no
+// subset exceeds.
+struct SubsetRing {
+  WorkItem* d_ring = nullptr;
+  WorkItem* d_captured = nullptr;
+  int64_t max_items = 0;
+  int64_t pos = 0;             // next free item of the ring
+  int64_t captured_used = 0;   // items of d_captured handed out
+  struct InFlight {
+    int64_t begin, end;
+    hipEvent_t done;
+  };
+  std::vector<InFlight> in_flight;       // oldest first
+  std::vector<hipEvent_t> idle_events;
+  std::mutex mu;                         // subset calls of one plan may come from several threads
+};
+
 // Appends the work items of `task_index` (record t) to out[class].  With
 // `fine` every block is cut into small-class sub-tiles.  Either cut gives the
 // same bits: both kernels shapes accumulate an output element in the same
@@ -132,9 +198,8 @@ struct cleave_plan {
   cleave::WorkItem* d_items[cleave::kNumTileClasses] = {nullptr, nullptr};
   cleave::WorkItem* d_items_fine = nullptr;
   cleave::ReduceItem* d_reduce_items = nullptr;
-  // Scratch for subset launches; grown on demand, reused by later calls.
-  cleave::WorkItem* d_subset_items = nullptr;
-  int64_t d_subset_capacity = 0;
+  // Work-item slices of subset launches (device memory sized once, at upload).
+  cleave::SubsetRing subset;
 
   // Tables and scratch of the returned-block check; created by its first call.
   cleave::VerifyTables* verify = nullptr;

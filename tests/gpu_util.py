@@ -50,3 +50,32 @@ def block_of(partials, task):
     off = int(task["partial_off"])
     ml, nl = int(task["m_len"]), int(task["n_len"])
     return partials[off:off + ml * nl].reshape(ml, nl)
+
+
+def elementwise_bound(rows, cols, k0, k1):
+    """Per-element bound on |fp32-accumulated block - fp64 block| for the block
+    rows[:, k0:k1] @ cols[k0:k1, :] of exactly representable inputs (products
+    of bf16 values are exact in fp32, so only the K additions round):
+
+        |err_ij| <= 8 * 2^-24 * ||a_i||_2 * ||b_j||_2      (norms over the chunk)
+
+    Rounding errors of a length-K fp32 accumulation add up like a random walk
+    over partial sums of size ~ sqrt(k) * rms(a) * rms(b); their standard
+    deviation is about 2^-24 * ||a_i|| * ||b_j|| / sqrt(2), so this is an
+    11-sigma bound (and far inside the deterministic K * 2^-24 * sum |a||b|).
+    Relative to the size of an output element it is ~5e-7 * sqrt(K): an
+    element wrong in its fifth digit fails, wherever it is."""
+    na = np.linalg.norm(rows[:, k0:k1], axis=1)
+    nb = np.linalg.norm(cols[k0:k1, :], axis=0)
+    return 8.0 * 2.0 ** -24 * np.outer(na, nb)
+
+
+def assert_elementwise(got, ref, bound, what):
+    """got (fp32 from the GPU) against ref (fp64 from the oracle), element by
+    element, plus the regression bar of 1e-5 in the Frobenius norm."""
+    diff = np.abs(got.astype(np.float64) - ref)
+    worst = np.argmax(diff - bound)
+    assert np.all(diff <= bound), (what, np.unravel_index(worst, diff.shape),
+                                   float(diff.reshape(-1)[worst]), float(bound.reshape(-1)[worst]))
+    den = np.linalg.norm(ref)
+    assert den == 0 or np.linalg.norm(diff) / den <= 1e-5, what

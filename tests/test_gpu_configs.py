@@ -2,10 +2,13 @@
 configuration the benchmark times (whole-plan execute + reduce per GEMM).
 
 A full fp64 oracle GEMM is used where it takes about a second; otherwise every
-GEMM is checked by (i) the fp64 random-projection identity over the whole of
-C, (ii) the full-K fp64 oracle on sampled output tiles (always including the
-last, ragged tile) and (iii) the per-task fp64 oracle on sampled partial
-blocks, plus the bitwise aggregation check on sampled tiles.
+GEMM of every configuration is checked by (i) the fp64 random-projection
+identity over the whole of C, (ii) the full-K fp64 oracle on sampled output
+tiles (always including the last, ragged tile) and (iii) the per-task fp64
+oracle on sampled partial blocks -- both against the contractual Frobenius bar
+and element by element against a bound derived from fp32 accumulation -- plus
+the bitwise aggregation check on sampled tiles.  The whole-output,
+every-element comparison at these sizes is in test_gpu_exact_full.py.
 """
 import numpy as np
 import pytest
@@ -17,7 +20,7 @@ from oracle import planner
 from workloads import layer_config, make_gemm_operands, draw_explicit_tiling, draw_reissue
 from workloads.configs import C4_TILING_SEED, C4_REISSUE_SEED
 
-from gpu_util import TOL, block_of
+from gpu_util import TOL, assert_elementwise, block_of, elementwise_bound
 
 pytestmark = pytest.mark.gpu
 
@@ -65,7 +68,12 @@ def check_gemm_sampled(g, plan, tasks, A, B, dA, dB, dtype, rng, n_tiles=2, full
         m0, ml, n0, nl = int(t0["m0"]), int(t0["m_len"]), int(t0["n0"]), int(t0["n_len"])
         ref = og.output_block(opA, opB, m0, ml, n0, nl)
         got = Ch[m0:m0 + ml, n0:n0 + nl]
-        assert og.rel_frobenius(got, ref) <= TOL[dtype], (g.name, tile)
+        assert og.rel_frobenius(got, ref) <= TOL[dtype], (g.name, tile)          # the contractual bar
+        rows, cols = opA[m0:m0 + ml, :], opB[:, n0:n0 + nl]
+        if dtype == "bf16":
+            # element by element: the S chunk sums and their S - 1 additions each round like one chunk
+            bound = sum(elementwise_bound(rows, cols, int(t["k0"]), int(t["k0"]) + int(t["k_len"])) for t in sel)
+            assert_elementwise(got, ref, bound + 2.0 ** -23 * len(sel) * np.abs(ref), (g.name, tile))
         # this tile's partial blocks: fetch only their slice of the buffer
         lo = int(t0["partial_off"])
         hi = lo + len(sel) * ml * nl
@@ -75,6 +83,10 @@ def check_gemm_sampled(g, plan, tasks, A, B, dA, dB, dtype, rng, n_tiles=2, full
         blk = og.task_block(opA, opB, sel[s_pick])
         got_blk = seg[s_pick * ml * nl:(s_pick + 1) * ml * nl].reshape(ml, nl)
         assert np.linalg.norm(got_blk - blk) <= TOL[dtype] * scale, (g.name, tile, s_pick)
+        if dtype == "bf16":
+            k0 = int(sel[s_pick]["k0"])
+            assert_elementwise(got_blk, blk, elementwise_bound(rows, cols, k0, k0 + int(sel[s_pick]["k_len"])),
+                               (g.name, tile, s_pick))
         # aggregation of this tile, bitwise
         local = sel.copy()
         local["partial_off"] -= lo
@@ -115,11 +127,7 @@ def test_c4_heterogeneous_tiles_and_reissue():
     cfg = layer_config("c4")
     dt = DeviceTensors(cfg)
     rng = np.random.default_rng(C4_TILING_SEED)
-    # one GEMM of each kind and shape family
-    names = ("q.fwd", "gate.fwd", "down.fwd", "down.dx", "gate.dx", "up.dw", "down.dw", "o.dw")
     for gid, g in enumerate(cfg.gemms):
-        if g.name not in names:
-            continue
         band_h, col_w, ks = draw_explicit_tiling(g.M, g.N, g.K, C4_TILING_SEED + gid)
         plan = cleave.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
         tasks, _ = planner.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
@@ -142,18 +150,14 @@ def test_c4_heterogeneous_tiles_and_reissue():
         print("c4", g.name, plan.num_tasks, "tasks,", len(lost), "re-issued", flush=True)
 
 
-def test_c5_llama13b_sampled_gemms():
+def test_c5_llama13b_layer():
     cfg = layer_config("c5")
     dt = DeviceTensors(cfg)
     rng = np.random.default_rng(cfg.seed)
     for gid, g in enumerate(cfg.gemms):
-        if g.name not in ("down.fwd", "q.dw"):
-            continue
         plan = cleave.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
         tasks, _ = planner.plan_uniform(g.M, g.N, g.K, cfg.tile_m, cfg.tile_n, cfg.ksplit, gemm_id=gid)
         assert plan.tasks.tobytes() == tasks.tobytes()
         A, B, dA, dB = dt.operands(g)
         check_gemm_sampled(g, plan, tasks, A, B, dA, dB, cfg.dtype, rng, n_tiles=2)
         print("c5", g.name, plan.num_tasks, "tasks", plan.last_kernel, flush=True)
-        dt.cpu.clear()
-        dt.dev.clear()

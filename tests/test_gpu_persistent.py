@@ -1,0 +1,66 @@
+"""The persistent multi-item path of the direct bf16 kernel, bit for bit.
+
+Every workgroup here runs several short work items in a row (more than twice
+as many items as the chip holds workgroups), so the code between two items is
+what is tested: the next item's ring fill issued ahead of the current item's
+stores, the shortened wait that relies on those stores, the item record
+fetched during the epilogue, the fall-back wait after a clipped (ragged)
+sub-tile followed again by full ones.  Chunks of 1, 2 and 3 K steps keep the
+K loop short, so nearly all of a launch is that code.  Integer-valued inputs:
+every partial block and the whole of C must equal the fp64 oracle exactly.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_22142_amd as cleave
+from oracle import gemm as og
+from oracle import planner
+from workloads.tensors import make_matrix
+
+from gpu_util import GpuGemm, block_of, stored
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
+K_STEP = 64          # elements of K the direct kernel consumes per step
+
+
+def _resident_workgroups(per_cu):
+    return torch.cuda.get_device_properties(0).multi_processor_count * per_cu
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("steps", [1, 2, 3])
+@pytest.mark.parametrize("cls", ["large", "small"])
+def test_many_short_items_per_workgroup_exact(cls, steps, transA, transB):
+    S = 2
+    K = K_STEP * steps * S
+    if cls == "large":
+        # 384 x 384 tiles are cut into a full 256 x 256 sub-tile and three clipped ones
+        # (256 x 128, 128 x 256, 128 x 128), so full and clipped items alternate in every
+        # workgroup; the last 40 columns form narrow tiles of the small class
+        M, N, tile = 6144, 4264, 384
+        per_cu, sub = 1, 256
+    else:
+        M, N, tile = 4160, 4104, 128
+        per_cu, sub = 2, 128
+    n_items = -(-M // sub) * -(-N // sub) * S
+    assert n_items > 2 * _resident_workgroups(per_cu), "the shape must give every workgroup several items"
+    a = make_matrix(500 + steps, M, K, "bf16", integer_valued=True)
+    b = make_matrix(600 + steps, K, N, "bf16", integer_valued=True)
+    plan = cleave.plan_uniform(M, N, K, tile, tile, S)
+    tasks, _ = planner.plan_uniform(M, N, K, tile, tile, S)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    run = GpuGemm(plan, stored(a, transA), stored(b, transB), transA, transB).run()
+    assert "direct" in plan.last_kernel and ("256x256" if cls == "large" else "128x128") in plan.last_kernel
+    parts, C = run.partials_host(), run.C_host()
+    opA, opB = og.logical_operands(stored(a, transA), transA, stored(b, transB), transB)
+    total = np.zeros((M, N))
+    for s in range(S):
+        ref = og.gemm(opA, opB, s * K // S, (s + 1) * K // S)
+        for t in tasks[tasks["ksplit_idx"] == s]:
+            m0, ml, n0, nl = int(t["m0"]), int(t["m_len"]), int(t["n0"]), int(t["n_len"])
+            assert np.array_equal(block_of(parts, t), ref[m0:m0 + ml, n0:n0 + nl]), (int(t["tile_id"]), s)
+        total += ref
+    assert np.array_equal(C, total)

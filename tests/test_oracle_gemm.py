@@ -187,3 +187,19 @@ def test_batch_view_is_the_head_slice_of_a_token_major_activation():
         assert np.array_equal(v, P[g * s_len:(g + 1) * s_len, :])
     with pytest.raises(ValueError):
         og.batch_view(Q, n_seq * H, H, s_len * ld, d, s_len, d)
+
+
+def test_rel_frobenius_hand_values():
+    # the yard-stick of every parity bar: ||C - C_ref||_F / ||C_ref||_F
+    ref = np.array([[3.0, 4.0]])                          # norm 5
+    assert og.rel_frobenius(np.array([[3.0, 4.05]]), ref) == pytest.approx(0.01, rel=1e-12)
+    ref = np.array([[1.0, 2.0], [2.0, 4.0]])              # norm sqrt(25) = 5
+    got = ref + np.array([[0.3, 0.0], [0.0, -0.4]])       # difference norm 0.5
+    assert og.rel_frobenius(got, ref) == pytest.approx(0.1, rel=1e-12)
+    # not symmetric in its arguments (the reference normalises), exact zero for equal inputs,
+    # absolute norm when the reference vanishes
+    assert og.rel_frobenius(ref, got) != pytest.approx(0.1, rel=1e-6)
+    assert og.rel_frobenius(ref, ref) == 0.0
+    assert og.rel_frobenius(np.array([[0.6, 0.8]]), np.zeros((1, 2))) == pytest.approx(1.0, rel=1e-12)
+    # fp32 input is widened, not rounded further
+    assert og.rel_frobenius(np.array([[3.0, 4.5]], dtype=np.float32), np.array([[3.0, 4.0]])) == pytest.approx(0.1, rel=1e-12)
