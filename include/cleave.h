@@ -58,7 +58,8 @@ typedef enum {
   CLEAVE_OK = 0,
   CLEAVE_EINVAL = -1, /* bad size, edge list, split count, pointer, leading dimension, enum */
   CLEAVE_ENOMEM = -2, /* host or device allocation of plan tables failed */
-  CLEAVE_EHIP = -3    /* a HIP runtime call failed; see cleave_last_hip_error */
+  CLEAVE_EHIP = -3,   /* a HIP runtime call failed; see cleave_last_hip_error */
+  CLEAVE_ELIMIT = -4  /* the request exceeds a fixed limit of the entry point */
 } cleave_status;
 
 typedef enum { CLEAVE_F32 = 0, CLEAVE_BF16 = 1 } cleave_dtype;
@@ -167,6 +168,30 @@ int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
                    const void* A, int64_t lda, int transA,
                    const void* B, int64_t ldb, int transB,
                    int dtype, float* partials, void* hip_stream);
+
+/* cleave_execute for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same result bits as cleave_execute, but the call never
+ * allocates or frees anything on the device or through the HIP runtime:
+ *   - the plan's tables must already be on the current device
+ *     (cleave_plan_upload, or any earlier execute / reduce of the plan);
+ *     otherwise CLEAVE_EINVAL -- this call does not upload;
+ *   - the work list of a subset (task_ids != NULL) is written into a fixed
+ *     768 KB array that is part of the library's code object (one copy per
+ *     GPU, held until the process ends) instead of plan-owned memory; a subset
+ *     whose tasks are cut into more than 16384 work items (256 x 256 or
+ *     128 x 128 sub-tiles of the tasks' blocks) is refused with CLEAVE_ELIMIT
+ *     and nothing is enqueued;
+ *   - every call on a GPU uses that GPU's one array, from its start: two
+ *     subset calls that may run at the same time on one GPU (different
+ *     streams, or threads) race and must be ordered by the caller; calls on
+ *     one stream are ordered by the stream.  No state is carried from call to
+ *     call: the array is overwritten by each call that uses it.
+ * With task_ids == NULL the whole plan runs (no work list is written). */
+int cleave_execute_noalloc(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                           const void* A, int64_t lda, int transA,
+                           const void* B, int64_t ldb, int transB,
+                           int dtype, float* partials, void* hip_stream);
 
 /* Batched form of cleave_execute for a plan made by cleave_plan_batched.
  * Member g = o * n_inner + i (0 <= i < n_inner, n_inner divides n_batch) reads

@@ -19,6 +19,7 @@ _BINDING_NAMES = (
     "EINVAL",
     "ENOMEM",
     "EHIP",
+    "ELIMIT",
     "CleaveError",
     "Device",
     "Plan",
@@ -32,6 +33,7 @@ _BINDING_NAMES = (
     "execute_assemble",
     "execute_batched",
     "execute_grouped",
+    "execute_noalloc",
     "plan_batched",
     "plan_explicit",
     "plan_uniform",

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libcleave.so")
 F32 = 0
 BF16 = 1
 
-OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
+OK, EINVAL, ENOMEM, EHIP, ELIMIT = 0, -1, -2, -3, -4
 
 # Byte layout of `cleave_task` (include/cleave.h).
 TASK_DTYPE = np.dtype([
@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc",
 )
 
 
@@ -87,6 +87,8 @@ def _load():
     lib.cleave_execute.argtypes = [p, p, i64, p, i64, ctypes.c_int, p, i64, ctypes.c_int,
                                    ctypes.c_int, p, p]
     lib.cleave_execute.restype = ctypes.c_int
+    lib.cleave_execute_noalloc.argtypes = lib.cleave_execute.argtypes
+    lib.cleave_execute_noalloc.restype = ctypes.c_int
     lib.cleave_reduce.argtypes = [p, p, p, i64, ctypes.c_int, p]
     lib.cleave_plan_batched.argtypes = [i64, i64, i64, i64, i64, i32, i64, ctypes.POINTER(p)]
     lib.cleave_plan_batched.restype = ctypes.c_int
@@ -226,9 +228,10 @@ def _matrix(t, what):
     return ctypes.c_void_p(t.data_ptr()), int(t.stride(0))
 
 
-def execute(plan, A, B, partials, transA=0, transB=0, task_ids=None, stream=None):
-    """cleave_execute: A, B stored device matrices (torch), partials a flat fp32
-    device tensor of plan.partial_elems elements."""
+def execute(plan, A, B, partials, transA=0, transB=0, task_ids=None, stream=None, noalloc=False):
+    """cleave_execute (or, with noalloc=True, cleave_execute_noalloc): A, B stored
+    device matrices (torch), partials a flat fp32 device tensor of
+    plan.partial_elems elements."""
     import torch
     a_ptr, lda = _matrix(A, "A")
     b_ptr, ldb = _matrix(B, "B")
@@ -246,9 +249,15 @@ def execute(plan, A, B, partials, transA=0, transB=0, task_ids=None, stream=None
     if task_ids is not None:
         ids = np.ascontiguousarray(task_ids, dtype=np.int64)
         ids_ptr, n_ids = ctypes.c_void_p(ids.ctypes.data), len(ids)
-    _check(_lib.cleave_execute(plan._h, ids_ptr, n_ids, a_ptr, lda, int(transA), b_ptr, ldb,
-                               int(transB), _dtype_code(A), ctypes.c_void_p(partials.data_ptr()),
-                               _stream_ptr(stream)), "cleave_execute")
+    entry = _lib.cleave_execute_noalloc if noalloc else _lib.cleave_execute
+    _check(entry(plan._h, ids_ptr, n_ids, a_ptr, lda, int(transA), b_ptr, ldb,
+                 int(transB), _dtype_code(A), ctypes.c_void_p(partials.data_ptr()),
+                 _stream_ptr(stream)), "cleave_execute_noalloc" if noalloc else "cleave_execute")
+
+
+def execute_noalloc(plan, A, B, partials, transA=0, transB=0, task_ids=None, stream=None):
+    """cleave_execute_noalloc: as execute, for callers that cannot allocate."""
+    execute(plan, A, B, partials, transA, transB, task_ids, stream, noalloc=True)
 
 
 def reduce(plan, partials, C, stream=None):

@@ -80,11 +80,21 @@ int upload_vector(const std::vector<T>& v, T** dst) {
   return CLEAVE_OK;
 }
 
-// Once per device and process: the execute kernels' dynamic-LDS limits and the
-// CU count.  Done when a plan's tables are uploaded, so that no launch has to.
+// Work-list memory of cleave_execute_noalloc: a fixed array in the code
+// object, one copy per GPU the library runs on, held until the process ends
+// (768 KB).  In host code the name is only a handle for hipGetSymbolAddress;
+// the address that kernels and copies use is g_static_scratch[device].
+constexpr int64_t kStaticScratchItems = 16384;
+static __device__ __align__(256) __attribute__((used))
+unsigned char scratch[kStaticScratchItems * sizeof(cleave::WorkItem)];
+
+// Once per device and process: the execute kernels' dynamic-LDS limits, the
+// CU count and the address of this device's copy of `scratch`.  Done when a
+// plan's tables are uploaded, so that no launch has to.
 constexpr int kMaxDevices = 64;
 std::mutex g_device_mu;
 int g_device_cus[kMaxDevices] = {};   // 0 = not initialised
+cleave::WorkItem* g_static_scratch[kMaxDevices] = {};
 
 int ensure_device_ready(int dev, int* cus) {
   if (dev < 0 || dev >= kMaxDevices) return CLEAVE_EINVAL;
@@ -92,6 +102,9 @@ int ensure_device_ready(int dev, int* cus) {
   if (g_device_cus[dev] == 0) {
     CLEAVE_HIP(cleave::configure_execute_kernels());
     CLEAVE_HIP(cleave::configure_execute_direct_kernels());
+    void* ptr = nullptr;   // `dev` is the current device: its copy of the array
+    CLEAVE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    g_static_scratch[dev] = static_cast<cleave::WorkItem*>(ptr);
     int n = 0;
     CLEAVE_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
     g_device_cus[dev] = std::max(n, 1);
@@ -303,19 +316,69 @@ struct AssembleTarget {
   int out_dtype = CLEAVE_F32;
 };
 
-// Enqueues the kernels that write the work items of `entries` to `out`.
-int expand_subset(const cleave_task* d_tasks, const std::vector<cleave::SubsetEntry>& entries, bool fine,
-                  cleave::WorkItem* out, hipStream_t stream) {
+// Where the work items of a subset go: one list per tile class, each in two
+// parts -- first the tasks whose chunk is a whole number of the direct
+// kernel's K steps, then the others -- with the caller's order kept inside
+// each part (the layout of the plan's own lists).
+struct SubsetLayout {
+  bool fine = false;                                  // every block cut into small-class sub-tiles
+  int64_t counts[cleave::kNumTileClasses][2] = {};    // work items per (class, part)
+  int64_t total() const { return counts[0][0] + counts[0][1] + counts[1][0] + counts[1][1]; }
+};
+inline int subset_part(const cleave_task& t) { return t.k_len % cleave::kDirectKStep == 0 ? 0 : 1; }
+
+// Validates the ids (range, no repeats) and sizes the lists.  Uses the plan's
+// own stamp array for the repeat check: no allocation.  Caller holds subset.mu.
+int layout_subset(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, int cus, SubsetLayout* out) {
+  const int64_t n_tasks = static_cast<int64_t>(plan->tasks.size());
+  if (++plan->seen_generation == 0) {   // wrapped: start over with clean stamps
+    std::fill(plan->seen_stamp.begin(), plan->seen_stamp.end(), 0u);
+    plan->seen_generation = 1;
+  }
+  size_t large_items = 0;
+  for (int64_t i = 0; i < n_ids; ++i) {
+    const int64_t id = task_ids[i];
+    if (id < 0 || id >= n_tasks || plan->seen_stamp[id] == plan->seen_generation) return CLEAVE_EINVAL;
+    plan->seen_stamp[id] = plan->seen_generation;
+    const cleave::SubTiling st = cleave::sub_tiling(plan->tasks[id], false);
+    if (st.cls == cleave::kTileLarge) large_items += st.count();
+  }
+  // Few large items would leave most CUs idle: cut everything small instead
+  // (the bits do not depend on the cut).
+  out->fine = large_items > 0 && large_items <= static_cast<size_t>(cus) / 2;
+  for (int64_t i = 0; i < n_ids; ++i) {
+    const cleave_task& t = plan->tasks[task_ids[i]];
+    const cleave::SubTiling st = cleave::sub_tiling(t, out->fine);
+    out->counts[st.cls][subset_part(t)] += st.count();
+  }
+  return CLEAVE_OK;
+}
+
+// Enqueues the kernels that write the subset's work items to `out`; the
+// (task, destination) pairs are built on the stack, one launch's worth at a time.
+int expand_subset(const cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                  const SubsetLayout& layout, cleave::WorkItem* out, hipStream_t stream) {
+  int64_t next[cleave::kNumTileClasses][2];
+  int64_t pos = 0;
+  for (int c = 0; c < cleave::kNumTileClasses; ++c)
+    for (int part = 0; part < 2; ++part) {
+      next[c][part] = pos;
+      pos += layout.counts[c][part];
+    }
   cleave::ExpandArgs ea{};
-  ea.tasks = d_tasks;
+  ea.tasks = plan->d_tasks;
   ea.out = out;
-  ea.fine = fine ? 1u : 0u;
-  for (size_t first = 0; first < entries.size(); first += cleave::kSubsetEntriesPerLaunch) {
-    const size_t n = std::min<size_t>(cleave::kSubsetEntriesPerLaunch, entries.size() - first);
-    ea.n_entries = static_cast<uint32_t>(n);
-    std::copy(entries.begin() + static_cast<std::ptrdiff_t>(first),
-              entries.begin() + static_cast<std::ptrdiff_t>(first + n), ea.entries);
-    CLEAVE_HIP(cleave::launch_expand_subset(ea, stream));
+  ea.fine = layout.fine ? 1u : 0u;
+  for (int64_t i = 0; i < n_ids; ++i) {
+    const cleave_task& t = plan->tasks[task_ids[i]];
+    const cleave::SubTiling st = cleave::sub_tiling(t, layout.fine);
+    int64_t& at = next[st.cls][subset_part(t)];
+    ea.entries[ea.n_entries++] = {static_cast<uint32_t>(task_ids[i]), static_cast<uint32_t>(at)};
+    at += st.count();
+    if (ea.n_entries == cleave::kSubsetEntriesPerLaunch || i + 1 == n_ids) {
+      CLEAVE_HIP(cleave::launch_expand_subset(ea, stream));
+      ea.n_entries = 0;
+    }
   }
   return CLEAVE_OK;
 }
@@ -323,7 +386,7 @@ int expand_subset(const cleave_task* d_tasks, const std::vector<cleave::SubsetEn
 int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, const void* A,
                  int64_t lda, int transA, const void* B, int64_t ldb, int transB, int dtype,
                  float* partials, const BatchLayout& bl, void* hip_stream,
-                 const AssembleTarget& asm_to = AssembleTarget{}) {
+                 const AssembleTarget& asm_to = AssembleTarget{}, bool static_scratch = false) {
   if (!plan || !A || !B || (!partials && !asm_to.C)) return CLEAVE_EINVAL;
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
@@ -344,53 +407,15 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     return large_items > 0 && large_items <= static_cast<size_t>(cus) / 2;
   };
 
-  // Subset: where each listed task's work items go.  One list per tile class,
-  // each in two parts -- first the tasks whose chunk is a whole number of the
-  // direct kernel's K steps, then the others -- with the caller's order kept
-  // inside each part (the layout of the plan's own lists).
-  std::vector<cleave::SubsetEntry> entries;
-  int64_t sub_counts[cleave::kNumTileClasses][2] = {};
-  bool fine = false;
-  if (task_ids) {
-    try {
-      std::vector<bool> seen(plan->tasks.size(), false);
-      size_t large_items = 0;
-      for (int64_t i = 0; i < n_ids; ++i) {
-        const int64_t id = task_ids[i];
-        if (id < 0 || id >= static_cast<int64_t>(plan->tasks.size()) || seen[id]) return CLEAVE_EINVAL;
-        seen[id] = true;
-        const cleave::SubTiling st = cleave::sub_tiling(plan->tasks[id], false);
-        if (st.cls == cleave::kTileLarge) large_items += st.count();
-      }
-      fine = prefers_fine(large_items);
-      const auto part_of = [](const cleave_task& t) { return t.k_len % cleave::kDirectKStep == 0 ? 0 : 1; };
-      for (int64_t i = 0; i < n_ids; ++i) {
-        const cleave_task& t = plan->tasks[task_ids[i]];
-        const cleave::SubTiling st = cleave::sub_tiling(t, fine);
-        sub_counts[st.cls][part_of(t)] += st.count();
-      }
-      int64_t next[cleave::kNumTileClasses][2];
-      int64_t pos = 0;
-      for (int c = 0; c < cleave::kNumTileClasses; ++c)
-        for (int part = 0; part < 2; ++part) {
-          next[c][part] = pos;
-          pos += sub_counts[c][part];
-        }
-      entries.reserve(static_cast<size_t>(n_ids));
-      for (int64_t i = 0; i < n_ids; ++i) {
-        const cleave_task& t = plan->tasks[task_ids[i]];
-        const cleave::SubTiling st = cleave::sub_tiling(t, fine);
-        int64_t& at = next[st.cls][part_of(t)];
-        entries.push_back({static_cast<uint32_t>(task_ids[i]), static_cast<uint32_t>(at)});
-        at += st.count();
-      }
-    } catch (const std::bad_alloc&) {
-      return CLEAVE_ENOMEM;
-    }
+  int dev = 0;
+  CLEAVE_HIP(hipGetDevice(&dev));
+  if (static_scratch) {
+    // this entry point never allocates: the tables must be on the device already
+    if (plan->device != dev) return CLEAVE_EINVAL;
+  } else {
+    rc = ensure_uploaded(plan);
+    if (rc != CLEAVE_OK) return rc;
   }
-
-  rc = ensure_uploaded(plan);
-  if (rc != CLEAVE_OK) return rc;
 
   // 16-byte load path: every chunk and tile edge a multiple of 16 bytes and
   // all rows of both operands starting on 16-byte boundaries.
@@ -423,30 +448,39 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   int64_t slice_begin = -1, slice_total = 0;
   if (task_ids) {
     subset_lock = std::unique_lock<std::mutex>(plan->subset.mu);
-    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-    CLEAVE_HIP(hipStreamIsCapturing(stream, &capture));
-    for (int c = 0; c < cleave::kNumTileClasses; ++c) slice_total += sub_counts[c][0] + sub_counts[c][1];
-    cleave::WorkItem* slice = nullptr;
-    rc = acquire_subset_slice(plan->subset, slice_total, capture != hipStreamCaptureStatusNone, &slice,
-                              &slice_begin);
+    SubsetLayout layout;
+    rc = layout_subset(plan, task_ids, n_ids, cus, &layout);
     if (rc != CLEAVE_OK) return rc;
-    rc = expand_subset(plan->d_tasks, entries, fine, slice, stream);
+    slice_total = layout.total();
+    cleave::WorkItem* slice = nullptr;
+    if (static_scratch) {
+      // the device's fixed array, from its start: whatever an earlier call left there is overwritten
+      if (slice_total > kStaticScratchItems) return CLEAVE_ELIMIT;
+      slice = g_static_scratch[dev];
+    } else {
+      hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+      CLEAVE_HIP(hipStreamIsCapturing(stream, &capture));
+      rc = acquire_subset_slice(plan->subset, slice_total, capture != hipStreamCaptureStatusNone, &slice,
+                                &slice_begin);
+      if (rc != CLEAVE_OK) return rc;
+    }
+    rc = expand_subset(plan, task_ids, n_ids, layout, slice, stream);
     if (rc != CLEAVE_OK) {
-      (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
+      if (!static_scratch) (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
       return rc;
     }
     int64_t pos = 0;
     for (int c = 0; c < cleave::kNumTileClasses; ++c) {
       d_lists[c] = slice + pos;
-      whole_steps[c] = sub_counts[c][0];
-      counts[c] = sub_counts[c][0] + sub_counts[c][1];
+      whole_steps[c] = layout.counts[c][0];
+      counts[c] = layout.counts[c][0] + layout.counts[c][1];
       pos += counts[c];
     }
   }
 
   // whatever has been enqueued reads the slice: mark it even if a later launch fails
   const auto launch_failed = [&](hipError_t e) {
-    if (task_ids) (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
+    if (task_ids && !static_scratch) (void)release_subset_slice(plan->subset, slice_begin, slice_total, stream);
     return hip_fail(e);
   };
   int64_t most = -1;
@@ -502,7 +536,7 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
                                                : kernel_name(dtype, c, vec, transA, transB);
     }
   }
-  if (task_ids) return release_subset_slice(plan->subset, slice_begin, slice_total, stream);
+  if (task_ids && !static_scratch) return release_subset_slice(plan->subset, slice_begin, slice_total, stream);
   return CLEAVE_OK;
 }
 
@@ -514,6 +548,15 @@ extern "C" int cleave_execute(cleave_plan* plan, const int64_t* task_ids, int64_
   if (plan && plan->batch > 0) return CLEAVE_EINVAL;   // batched plans use the batched call
   return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials,
                       BatchLayout{}, hip_stream);
+}
+
+extern "C" int cleave_execute_noalloc(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,
+                                      const void* A, int64_t lda, int transA, const void* B,
+                                      int64_t ldb, int transB, int dtype, float* partials,
+                                      void* hip_stream) {
+  if (plan && plan->batch > 0) return CLEAVE_EINVAL;
+  return execute_impl(plan, task_ids, n_ids, A, lda, transA, B, ldb, transB, dtype, partials,
+                      BatchLayout{}, hip_stream, AssembleTarget{}, true);
 }
 
 extern "C" int cleave_execute_batched(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids,

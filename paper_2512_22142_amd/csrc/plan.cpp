@@ -205,6 +205,7 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
     }
     }
     p->partial_elems = static_cast<int64_t>(off);
+    p->seen_stamp.assign(p->tasks.size(), 0u);
 
     for (const cleave_task& t : p->tasks) {
       const uint32_t k_or = t.k0 | t.k_len;
@@ -361,6 +362,7 @@ extern "C" const char* cleave_strerror(int status) {
     case CLEAVE_EINVAL: return "invalid argument";
     case CLEAVE_ENOMEM: return "out of memory";
     case CLEAVE_EHIP: return "HIP runtime error";
+    case CLEAVE_ELIMIT: return "request exceeds the fixed limit of this entry point";
     default: return "unknown status";
   }
 }

@@ -200,6 +200,11 @@ struct cleave_plan {
   cleave::ReduceItem* d_reduce_items = nullptr;
   // Work-item slices of subset launches (device memory sized once, at upload).
   cleave::SubsetRing subset;
+  // Repeat check of a subset's task ids without clearing or allocating: task i
+  // was listed in the current call iff seen_stamp[i] == seen_generation (one
+  // entry per task, made with the plan; guarded by subset.mu).
+  std::vector<uint32_t> seen_stamp;
+  uint32_t seen_generation = 0;
 
   // Tables and scratch of the returned-block check; created by its first call.
   cleave::VerifyTables* verify = nullptr;
