@@ -13,6 +13,7 @@ step's wall time (execute + reduce), `roofline` describes the execute kernel
 the same tasks.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -50,50 +51,12 @@ def kernel_sources_digest():
     return h.hexdigest()
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--group-levels", action="store_true",
-                    help="one grouped launch per set of same-shape GEMMs of a DAG level (12 launches "
-                         "per c3 step instead of 21); measured: execute +1 %, reduce -3 %, step time equal")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
-    ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
-    ap.add_argument("--no-attention", action="store_true", help="skip the batched attention-product leg")
-    ap.add_argument("--no-epilogues", action="store_true", help="skip the fused Adam / residual leg")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
-                         "reading for the FETCH_SIZE / WRITE_SIZE counters) and exit")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this path runs on one GPU only (tasks are independent and would "
-                 "shard by output tile without any exchange); run with --gpus 1")
-
-    import numpy as np
-    import torch
-
-    from paper_2512_22142_amd.build import ensure_built
-    ensure_built()                      # uses the built library; builds only if there is none
-    import paper_2512_22142_amd as cleave
+def measure_layer(cleave, torch, config_name, steps, warmup, group_levels=False):
+    """Builds one configuration's resident inputs, plans and workspace, runs
+    `warmup` untimed and `steps` timed steps (every GEMM of the layer: execute
+    then reduce) and returns the measurements as a dict of local names."""
     from workloads import layer_config, make_gemm_operands
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    torch.cuda.set_device(0)
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(10):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4,
-                          "launches": 10}))
-        return
-    cfg = layer_config(args.config)
+    cfg = layer_config(config_name)
     in_bytes = 2 if cfg.dtype == "bf16" else 4
 
     # ---- resident inputs, plans, workspace --------------------------------
@@ -104,7 +67,7 @@ def main():
         for name, t in ((g.a, A), (g.b, B)):
             if name not in dev:
                 dev[name] = t.cuda()
-        if args.config == "c4":
+        if config_name == "c4":
             # heterogeneous guillotine tiling with a K-split per tile, drawn per GEMM
             from workloads import draw_explicit_tiling
             from workloads.configs import C4_TILING_SEED
@@ -136,7 +99,7 @@ def main():
     # projections; gate and up) as one grouped execute and one grouped reduce
     # launch over a shared task list.  Uniform tilings only: c4 draws a
     # different tiling per GEMM.
-    grouping = args.group_levels and args.config != "c4"
+    grouping = group_levels and config_name != "c4"
     groups, open_group = [], {}
     for i, (g, _, _, _) in enumerate(gemms):
         key = (g.level, g.kind, g.M, g.N, g.K, g.transA, g.transB)
@@ -189,7 +152,7 @@ def main():
                 events.append((i, prev, mid, end))
                 prev = end
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
@@ -200,24 +163,24 @@ def main():
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
     t_begin.record(stream)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(events)
     t_end.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     gpu_ms = t_begin.elapsed_time(t_end)
-    ms_per_step = max(gpu_ms, wall * 1e3) / args.steps
+    ms_per_step = max(gpu_ms, wall * 1e3) / steps
 
     exec_ms = [0.0] * len(launches)
     red_ms = [0.0] * len(launches)
     for i, e0, e1, e2 in events:
         exec_ms[i] += e0.elapsed_time(e1)
         red_ms[i] += e1.elapsed_time(e2)
-    exec_ms = [x / args.steps for x in exec_ms]
-    red_ms = [x / args.steps for x in red_ms]
+    exec_ms = [x / steps for x in exec_ms]
+    red_ms = [x / steps for x in red_ms]
     # each step on its own: first event of the step to its last
     n_g = len(launches)
-    step_ms = sorted(events[k * n_g][1].elapsed_time(events[k * n_g + n_g - 1][3]) for k in range(args.steps))
+    step_ms = sorted(events[k * n_g][1].elapsed_time(events[k * n_g + n_g - 1][3]) for k in range(steps))
     step_median = (step_ms[(len(step_ms) - 1) // 2] + step_ms[len(step_ms) // 2]) / 2
 
     flops = [L["flops"] for L in launches]
@@ -229,10 +192,67 @@ def main():
     red_gbps = sum(red_bytes) / (red_total_ms * 1e-3) / 1e9
     value = total_flops / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
-    counters_valid = (args.config == COUNTER_TRAFFIC["workload"] and not grouping and
+    counters_valid = (config_name == COUNTER_TRAFFIC["workload"] and not grouping and
                       kernel_sources_digest() == COUNTER_TRAFFIC["sources_sha256"])
     exec_traffic = round(COUNTER_TRAFFIC["execute_bytes_per_launch"]) if counters_valid else None
     red_traffic = round(COUNTER_TRAFFIC["reduce_bytes_per_launch"]) if counters_valid else None
+
+    return dict(locals())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--group-levels", action="store_true",
+                    help="one grouped launch per set of same-shape GEMMs of a DAG level (12 launches "
+                         "per c3 step instead of 21); measured: execute +1 %, reduce -3 %, step time equal")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--no-verify", action="store_true", help="skip the returned-block check leg")
+    ap.add_argument("--no-attention", action="store_true", help="skip the batched attention-product leg")
+    ap.add_argument("--no-epilogues", action="store_true", help="skip the fused Adam / residual leg")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
+    ap.add_argument("--other-steps", type=int, default=5)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
+                         "reading for the FETCH_SIZE / WRITE_SIZE counters) and exit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on one GPU only (tasks are independent and would "
+                 "shard by output tile without any exchange); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2512_22142_amd.build import ensure_built
+    ensure_built()                      # uses the built library; builds only if there is none
+    import paper_2512_22142_amd as cleave
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4,
+                          "launches": 10}))
+        return
+    m = measure_layer(cleave, torch, args.config, args.steps, args.warmup, args.group_levels)
+    (cfg, in_bytes, cpu, gemms, launches, workspace, slots, outputs, stream, step, grouping) = (
+        m[k] for k in ("cfg", "in_bytes", "cpu", "gemms", "launches", "workspace", "slots", "outputs",
+                       "stream", "step", "grouping"))
+    (ms_per_step, step_median, step_ms, exec_ms, red_ms, flops, red_bytes, total_flops, exec_total_ms,
+     red_total_ms, exec_tflops, red_gbps, value, peak, exec_traffic, red_traffic) = (
+        m[k] for k in ("ms_per_step", "step_median", "step_ms", "exec_ms", "red_ms", "flops", "red_bytes",
+                       "total_flops", "exec_total_ms", "red_total_ms", "exec_tflops", "red_gbps", "value",
+                       "peak", "exec_traffic", "red_traffic"))
 
     per_launch = [{"gemms": L["name"], "tasks": L["tasks"], "kernel": L["plan"].last_kernel,
                    "execute_ms": round(exec_ms[i], 4), "execute_tflops": round(flops[i] / exec_ms[i] / 1e9, 1),
@@ -478,6 +498,30 @@ def main():
             "note": "bytes = 4*S per element of partials + 26 per parameter (fp32 w, m, v read and written, "
                     "bf16 copy written); the gradient is never stored",
         }
+
+    # ---- the other configurations, a few steps each (reported, not `value`) ---
+    if not args.no_other_configs:
+        others = {}
+        for name in ("c1", "c2", "c4", "c5"):
+            if name == args.config:
+                continue
+            o = measure_layer(cleave, torch, name, args.other_steps, 2)
+            o_peak = o["peak"]
+            others[name] = {
+                "workload": o["cfg"].name, "dtype": o["cfg"].dtype, "steps": args.other_steps,
+                "gemms": len(o["gemms"]), "tasks": sum(p.num_tasks for _, p, _, _ in o["gemms"]),
+                "ms_per_step": round(o["ms_per_step"], 4), "tflops": round(o["value"], 2),
+                "execute_ms": round(o["exec_total_ms"], 4), "execute_tflops": round(o["exec_tflops"], 2),
+                "execute_frac_mfma_peak": round(o["exec_tflops"] / o_peak, 4),
+                "reduce_ms": round(o["red_total_ms"], 4), "reduce_gbps": round(o["red_gbps"], 1),
+                "reduce_frac_hbm_peak": round(o["red_gbps"] / PEAK_HBM_GBPS, 4),
+            }
+            if name == "c1":
+                others[name]["note"] = "3 MiB of partials: cache-resident, not an HBM measurement"
+            del o
+            gc.collect()
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
 
     # ---- CPU baseline: the oracle as it stands, bounded sample -------------
     if not args.no_cpu_baseline:
