@@ -261,25 +261,110 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       if (st < c.steps) issue(c, st, st);
   };
 
-  // Work items are walked with the grid as stride.  The record of the next
-  // item is read (one level of scalar loads) at the start of this item's
-  // epilogue; holding it in registers across the K loop instead cost more in
-  // spills than the load latency it hid.
+  // Work items are walked with the grid as stride.  The ring runs on across
+  // items: when the current item and the next one are both full sub-tiles, the
+  // next item's first two K steps are fetched into the ring stages that this
+  // item's last two steps free, exactly as this item's own later steps would
+  // be, so the next K loop starts without a ring fill and without waiting for
+  // this item's stores.  Otherwise (clipped sub-tiles need other lane offsets,
+  // one-step items free no stage early) the ring is filled from empty after the
+  // item's last step, ahead of its stores.
+  static_assert(STAGES == 2, "the hand-over between items is written for a ring of two stages");
+  constexpr int kTileStores = full_tile_stores<MB, NB>();   // store instructions per lane and full sub-tile
+  constexpr int kHalfStores = kTileStores / 2;
+  constexpr int kBehindCheck = kHalfStores < 63 ? kHalfStores : 63;
+  static_assert(MB % 2 == 0, "the epilogue stores a sub-tile in two halves of block rows");
+
   const int64_t stride = gridDim.x;
   if (static_cast<int64_t>(blockIdx.x) >= args.n_items) return;
   ItemCtx c = make_ctx(load_item(blockIdx.x));
   fill_ring(c);
   int64_t it_next = static_cast<int64_t>(blockIdx.x) + stride;
-  // True when this item's ring fill was followed by the previous item's full
-  // epilogue: more stores than the vector-memory counter can hold (63) were
-  // issued after those loads, and the counter retires in issue order, so the
-  // loads have landed once the stores have all been issued.
-  bool fill_landed = false;
+  // How the current item's first two steps got into the ring.
+  //   kFilled:             ring filled from empty, nothing issued since.
+  //   kFilledBehindStores: ring filled from empty, then the previous item's
+  //     stores: more of them than the vector-memory counter can hold (63), and
+  //     the counter retires in issue order, so the loads have landed once at
+  //     most 63 operations are outstanding.
+  //   kPrefetched:         fetched during the previous item's last two steps;
+  //     step 0 was waited for at that item's last barrier (its first fragments
+  //     are already in registers), step 1 between the two halves of its stores.
+  enum Entry : int { kFilled = 0, kFilledBehindStores = 1, kPrefetched = 2 };
+  int entry = kFilled;
+  int phase = 0;   // ring stage that holds the current item's step 0
+
+  f32x16 acc[MB][NB];
+  u32x4 fa[2][MB], fb[2][NB];
+
+  // Fragment reads are ordinary (compiler-visible) LDS loads: the compiler
+  // tracks their completion, and every address is a lane-constant register
+  // plus a compile-time offset (stage, block, sub-step).
+  auto tr_read = [&](const unsigned char* p) -> u32x2 {
+    return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)p));
+  };
+  // Fragments of sub-step KS of the ring stage at byte offset `stage` into
+  // register set `buf`.
+  auto read_frags = [&](uint32_t stage, auto ks_tag, int buf) {
+    constexpr int KS = decltype(ks_tag)::value;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      if constexpr (A_K) {
+        fa[buf][i] = *reinterpret_cast<const u32x4*>(smem + (a_addr[KS] + stage) + i * 32 * kRowBytes);
+      } else {
+        const unsigned char* p = smem + (a_addr[i] + stage) + KS * (16 * CHA * 16);
+        const u32x2 lo = tr_read(p);
+        const u32x2 hi = tr_read(p + 4 * CHA * 16);
+        fa[buf][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      if constexpr (B_K) {
+        fb[buf][j] = *reinterpret_cast<const u32x4*>(smem + (b_addr[KS] + stage) + j * 32 * kRowBytes);
+      } else {
+        const unsigned char* p = smem + (b_addr[j] + stage) + KS * (16 * CHB * 16);
+        const u32x2 lo = tr_read(p);
+        const u32x2 hi = tr_read(p + 4 * CHB * 16);
+        fb[buf][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+    }
+  };
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]),
+            acc[i][j], 0, 0, 0);
+  };
+
+  // Instruction order of one sub-step, as a hint to the scheduler: the MFMAs
+  // of the current fragments with the LDS reads of the next fragments spread
+  // one (or two, for transpose reads) behind each of them, the last two
+  // MFMAs without reads.  Measured +2 % over the compiler's own order.
+  auto interleave = [&]() {
+    constexpr int kReads = (A_K ? MB : 2 * MB) + (B_K ? NB : 2 * NB);
+    constexpr int kMfma = MB * NB;
+    constexpr int kTail = kMfma > 2 ? 2 : kMfma - 1;             // MFMAs without reads behind them
+    constexpr int kPer = (kReads + (kMfma - kTail) - 1) / (kMfma - kTail);
+#pragma unroll
+    for (int i = 0; i < kMfma; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one MFMA
+      if (i < kMfma - kTail) __builtin_amdgcn_sched_group_barrier(0x100, kPer, 0);   // LDS reads
+    }
+  };
 
   for (;;) {
     const int steps = c.steps;
+    const bool has_next = it_next < args.n_items;
+    // The next item's record: one level of scalar loads through the constant
+    // address space, needed two steps before this item ends.
+    const ItemCtx nx = make_ctx(load_item(has_next ? it_next : it_next - stride));
+    const bool interior = c.m_valid == TM && c.n_valid == TN;
+    // hand the ring over without draining it
+    const bool cont = has_next && interior && nx.m_valid == TM && nx.n_valid == TN && steps >= 2;
 
-    f32x16 acc[MB][NB];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -287,92 +372,37 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    u32x4 fa[2][MB], fb[2][NB];
-
-    // Fragment reads are ordinary (compiler-visible) LDS loads: the compiler
-    // tracks their completion, and every address is a lane-constant register
-    // plus a compile-time offset (stage, block, sub-step).
-    auto tr_read = [&](const unsigned char* p) -> u32x2 {
-      return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)p));
-    };
-    // Fragments of sub-step KS of ring stage ST into register set `buf`.
-    auto read_frags = [&](auto st, auto ks_tag, int buf) {
-      constexpr int ST = decltype(st)::value;
-      constexpr int KS = decltype(ks_tag)::value;
-#pragma unroll
-      for (int i = 0; i < MB; ++i) {
-        if constexpr (A_K) {
-          fa[buf][i] = *reinterpret_cast<const u32x4*>(smem + a_addr[KS] + ST * kStage +
-                                                       i * 32 * kRowBytes);
-        } else {
-          const unsigned char* p = smem + a_addr[i] + ST * kStage + KS * (16 * CHA * 16);
-          const u32x2 lo = tr_read(p);
-          const u32x2 hi = tr_read(p + 4 * CHA * 16);
-          fa[buf][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        if constexpr (B_K) {
-          fb[buf][j] = *reinterpret_cast<const u32x4*>(smem + b_addr[KS] + ST * kStage +
-                                                       j * 32 * kRowBytes);
-        } else {
-          const unsigned char* p = smem + b_addr[j] + ST * kStage + KS * (16 * CHB * 16);
-          const u32x2 lo = tr_read(p);
-          const u32x2 hi = tr_read(p + 4 * CHB * 16);
-          fb[buf][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-        }
-      }
-    };
-    auto mma = [&](int buf) {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]),
-              acc[i][j], 0, 0, 0);
-    };
-
-    // Instruction order of one sub-step, as a hint to the scheduler: the MFMAs
-    // of the current fragments with the LDS reads of the next fragments spread
-    // one (or two, for transpose reads) behind each of them, the last two
-    // MFMAs without reads.  Measured +2 % over the compiler's own order.
-    auto interleave = [&]() {
-      constexpr int kReads = (A_K ? MB : 2 * MB) + (B_K ? NB : 2 * NB);
-      constexpr int kMfma = MB * NB;
-      constexpr int kTail = kMfma > 2 ? 2 : kMfma - 1;             // MFMAs without reads behind them
-      constexpr int kPer = (kReads + (kMfma - kTail) - 1) / (kMfma - kTail);
-#pragma unroll
-      for (int i = 0; i < kMfma; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one MFMA
-        if (i < kMfma - kTail) __builtin_amdgcn_sched_group_barrier(0x100, kPer, 0);   // LDS reads
-      }
-    };
-
     // Step 0 must have landed.  All earlier fragment reads of this workgroup
     // completed before the previous item's final barrier.
-    if (fill_landed) {
-      CLEAVE_WAIT_BARRIER(63);
-    } else if (steps >= STAGES) {
-      CLEAVE_WAIT_BARRIER((STAGES - 1) * LPS);
-    } else {
-      CLEAVE_WAIT_BARRIER(0);
+    if (entry != kPrefetched) {
+      if (entry == kFilledBehindStores) {
+        CLEAVE_WAIT_BARRIER(63);
+      } else if (steps >= STAGES) {
+        CLEAVE_WAIT_BARRIER(LPS);
+      } else {
+        CLEAVE_WAIT_BARRIER(0);
+      }
+      read_frags(0u, int_c<0>{}, 0);   // a ring filled from empty starts at stage 0
     }
-    read_frags(int_c<0>{}, int_c<0>{}, 0);
 
-    // One K step out of ring stage ST.  Sub-step j multiplies register set
-    // j & 1 while the fragments of sub-step j+1 are fetched into the other
-    // set.  The barrier sits before the last sub-step's MFMAs: by then this
-    // wave holds all fragments of step s and step s+1 has landed (loads return
-    // in order; only the STAGES-2 younger steps may still be in flight), so
-    // stage ST is refilled with step s+STAGES and the first fragments of step
-    // s+1 are fetched while the last sub-step multiplies.
-    auto k_step = [&](auto st, int s) {
-      constexpr int ST = decltype(st)::value;
+    // One K step; step s sits in ring stage (s + phase) % 2.  Sub-step j
+    // multiplies register set j & 1 while the fragments of sub-step j+1 are
+    // fetched into the other set.  The barrier sits before the last sub-step's
+    // MFMAs: by then this wave holds all fragments of step s and the step
+    // after it has landed (loads return in order), so the stage is refilled
+    // with the step after next -- this item's, or the next item's first or
+    // second -- and the first fragments of the following step are fetched
+    // while the last sub-step multiplies.  MID: a step with at least two more
+    // steps of this item behind it and not the item's first -- no case
+    // distinctions, the loop body of long chunks.
+    auto k_step = [&](auto mid_tag, int s) {
+      constexpr bool MID = decltype(mid_tag)::value;
+      const int st = (s + phase) & 1;
+      const uint32_t cur = st ? kStage : 0;
+      const uint32_t oth = st ? 0 : kStage;
       auto sub = [&](auto j_tag) {
         constexpr int J = decltype(j_tag)::value;
-        read_frags(st, int_c<J + 1>{}, (J + 1) & 1);
+        read_frags(cur, int_c<J + 1>{}, (J + 1) & 1);
         mma(J & 1);
         interleave();
       };
@@ -381,55 +411,66 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         sub(int_c<1>{});
         sub(int_c<2>{});
       }
-      if ((fill_landed && s + 1 < STAGES) || s + 1 >= steps) {
-        // step s+1 belongs to the ring fill, or there is no step s+1: nothing to
-        // wait for, and no reason to wait for the previous item's stores either
-        CLEAVE_WAIT_BARRIER(63);
-      } else if (s + STAGES - 1 < steps) {
-        CLEAVE_WAIT_BARRIER((STAGES - 2) * LPS);
-      } else {
+      if constexpr (MID) {
         CLEAVE_WAIT_BARRIER(0);
+        issue(c, s + STAGES, st);
+        read_frags(oth, int_c<0>{}, 0);
+      } else {
+        const bool last = s + 1 >= steps;
+        if (last && !cont) {
+          // no step follows in the ring: nothing to wait for, and no reason to
+          // wait for the previous item's stores either
+          CLEAVE_WAIT_BARRIER(63);
+        } else if (s == 0 && entry == kFilledBehindStores) {
+          CLEAVE_WAIT_BARRIER(63);
+        } else if (s == 0 && entry == kPrefetched) {
+          // step 1 was waited for before the second half of the previous item's stores
+          CLEAVE_WAIT_BARRIER(kBehindCheck);
+        } else {
+          CLEAVE_WAIT_BARRIER(0);
+        }
+        if (s + STAGES < steps) {
+          issue(c, s + STAGES, st);
+        } else if (cont && s + STAGES - steps < nx.steps) {
+          issue(nx, s + STAGES - steps, st);
+        }
+        if (!last || cont) read_frags(oth, int_c<0>{}, 0);
       }
-      if (s + STAGES < steps) issue(c, s + STAGES, ST);
-      if (s + 1 < steps) read_frags(int_c<(ST + 1) % STAGES>{}, int_c<0>{}, 0);
       mma((kSub - 1) & 1);
       interleave();
     };
-    int s = 0;
-    for (; s + STAGES <= steps; s += STAGES) {
-      k_step(int_c<0>{}, s);
-      k_step(int_c<1>{}, s + 1);
-      if constexpr (STAGES > 2) k_step(int_c<2>{}, s + 2);
-      if constexpr (STAGES > 3) k_step(int_c<3>{}, s + 3);
-      if constexpr (STAGES > 4) k_step(int_c<4>{}, s + 4);
-    }
-    if (s < steps) k_step(int_c<0>{}, s);
-    if constexpr (STAGES > 2) {
-      if (s + 1 < steps) k_step(int_c<1>{}, s + 1);
-    }
-    if constexpr (STAGES > 3) {
-      if (s + 2 < steps) k_step(int_c<2>{}, s + 2);
-    }
-    if constexpr (STAGES > 4) {
-      if (s + 3 < steps) k_step(int_c<3>{}, s + 3);
-    }
+    k_step(std::false_type{}, 0);
+    int s = 1;
+    for (; s + STAGES < steps; ++s) k_step(std::true_type{}, s);
+    for (; s < steps; ++s) k_step(std::false_type{}, s);
 
     // Every wave is past the last step's barrier, hence past all of its
-    // fragment reads: the ring is free.  The next item's ring fill is issued
-    // before this item's stores so that its latency hides behind them.
+    // fragment reads of this item.
     const int row0 = wm * S::WTM + lh * 4;
     const int col0 = wn * S::WTN + l32;
     const TileTarget target = c.out;
     const int m_valid = c.m_valid, n_valid = c.n_valid;
-    const bool interior = m_valid == TM && n_valid == TN;
-    const bool has_next = it_next < args.n_items;
-    const ItemCtx nx = make_ctx(load_item(has_next ? it_next : it_next - stride));
-    if (has_next) fill_ring(nx);
     const bool bf16_out = args.C && args.c_bf16;
-    store_tile<MB, NB>(acc, target, bf16_out, row0, col0, m_valid, n_valid, interior);
+    if (cont) {
+      // The next item's step 1 went out at the last barrier; wait for it
+      // between the two halves of the stores: the first half keeps the memory
+      // pipeline busy meanwhile, and the second half then trails the check, so
+      // that the next item's first barrier finds at most kBehindCheck
+      // operations outstanding without any store having to complete.
+      store_tile_rows<MB, NB, 0, MB / 2>(acc, target, bf16_out, row0, col0);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kBehindCheck) : "memory");
+      store_tile_rows<MB, NB, MB / 2, MB>(acc, target, bf16_out, row0, col0);
+      entry = kPrefetched;
+      phase = (phase + steps) & 1;
+    } else {
+      // The ring is free: the next item's ring fill is issued before this
+      // item's stores so that its latency hides behind them.
+      if (has_next) fill_ring(nx);
+      store_tile<MB, NB>(acc, target, bf16_out, row0, col0, m_valid, n_valid, interior);
+      entry = (interior && kTileStores >= 63) ? kFilledBehindStores : kFilled;
+      phase = 0;
+    }
     if (!has_next) break;
-    // the shortcut of the next item's first waits needs at least 63 stores behind the ring fill
-    fill_landed = interior && full_tile_stores<MB, NB>() >= 63;
     c = nx;
     it_next += stride;
   }

@@ -86,6 +86,36 @@ __device__ __forceinline__ void store_blocks(const tile_f32x16 (&acc)[MB][NB], T
   }
 }
 
+// Block rows [I0, I1) of a full sub-tile (no bounds checks), same order and
+// addresses as store_blocks: lets a caller put other work between two parts
+// of a sub-tile's stores.
+template <int MB, int NB, int I0, int I1, typename T, typename Cvt>
+__device__ __forceinline__ void store_block_rows(const tile_f32x16 (&acc)[MB][NB], T* tp, int64_t ld,
+                                                 Cvt cvt) {
+#pragma unroll
+  for (int i = I0; i < I1; ++i)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        T* p = tp + static_cast<int64_t>(i * 32 + q * 8 + r) * ld;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) p[j * 32] = cvt(acc[i][j][q * 4 + r]);
+      }
+}
+
+template <int MB, int NB, int I0, int I1>
+__device__ __forceinline__ void store_tile_rows(const tile_f32x16 (&acc)[MB][NB], const TileTarget& t,
+                                                bool bf16, int row0, int col0) {
+  if (!bf16) {
+    float* tp = reinterpret_cast<float*>(t.base) + row0 * t.ld + col0;
+    store_block_rows<MB, NB, I0, I1>(acc, tp, t.ld, [](float x) { return x; });
+  } else {
+    uint16_t* tp = reinterpret_cast<uint16_t*>(t.base) + row0 * t.ld + col0;
+    store_block_rows<MB, NB, I0, I1>(acc, tp, t.ld, [](float x) { return tile_to_bf16(x); });
+  }
+}
+
 // Number of store instructions a lane issues for a full sub-tile.
 template <int MB, int NB>
 __device__ __forceinline__ constexpr int full_tile_stores() {
