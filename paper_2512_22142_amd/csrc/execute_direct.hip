@@ -280,6 +280,13 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   ItemCtx c = make_ctx(load_item(blockIdx.x));
   fill_ring(c);
   int64_t it_next = static_cast<int64_t>(blockIdx.x) + stride;
+  // Item records are read two items ahead (scalar loads through the constant
+  // address space): the read for the item after next is issued right behind
+  // the current item's first barrier, a whole K step before the next wait
+  // that covers it.  `last_item` stands in for records past the end.
+  const int64_t last_item = args.n_items - 1;
+  ItemCtx nx = make_ctx(load_item(it_next < args.n_items ? it_next : last_item));
+  WorkItem after_next;
   // How the current item's first two steps got into the ring.
   //   kFilled:             ring filled from empty, nothing issued since.
   //   kFilledBehindStores: ring filled from empty, then the previous item's
@@ -358,9 +365,6 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   for (;;) {
     const int steps = c.steps;
     const bool has_next = it_next < args.n_items;
-    // The next item's record: one level of scalar loads through the constant
-    // address space, needed two steps before this item ends.
-    const ItemCtx nx = make_ctx(load_item(has_next ? it_next : it_next - stride));
     const bool interior = c.m_valid == TM && c.n_valid == TN;
     // hand the ring over without draining it
     const bool cont = has_next && interior && nx.m_valid == TM && nx.n_valid == TN && steps >= 2;
@@ -434,6 +438,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         } else if (cont && s + STAGES - steps < nx.steps) {
           issue(nx, s + STAGES - steps, st);
         }
+        if (s == 0) after_next = load_item(it_next + stride < args.n_items ? it_next + stride : last_item);
         if (!last || cont) read_frags(oth, int_c<0>{}, 0);
       }
       mma((kSub - 1) & 1);
@@ -472,6 +477,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     }
     if (!has_next) break;
     c = nx;
+    nx = make_ctx(after_next);
     it_next += stride;
   }
 }
