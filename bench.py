@@ -35,8 +35,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "9bfec9d12d2c4fcdefe59ac1a131b9ffd6400cb2e30989c91369ba6411c0cc8a",
-    "execute_bytes_per_launch": (2.0 * 241521 + 394338) * 1024,
+    "sources_sha256": "4ec236cdf7456416383dc4106118f8a8bc1d4ab17c5ef43a954d80c3c0d434ae",
+    "execute_bytes_per_launch": (2.0 * 225531 + 388535) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194739 + 97134) * 1024,
 }
 
