@@ -375,6 +375,24 @@ int cleave_reassign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
                     int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
                     int32_t* tile_device, double* cost);
 
+/* The churn re-solve with general cache sets (paper Sec. 4.2: binary cache
+ * matrices R_s over the rows of A and C_s over the columns of B, one row per
+ * device): survivor k holds the rows in the union of its n_row_iv[k] intervals
+ * and the columns in the union of its n_col_iv[k] intervals.  row_iv lists the
+ * devices' row intervals one after the other as pairs [lo, hi) (absolute
+ * indices, per device ascending and disjoint), col_iv likewise; a device with
+ * no cached rows has n_row_iv[k] = 0.  The downlink term of a shard counts
+ * only the rows and columns outside the owner's sets.  Everything else as for
+ * cleave_reassign, which is the special case of one interval each.
+ * CLEAVE_EINVAL also for negative counts, unsorted or overlapping intervals. */
+int cleave_reassign_sets(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                         const cleave_device* devs, int32_t n_devs, int64_t granule,
+                         int64_t row0, int64_t col0,
+                         const int32_t* n_row_iv, const int64_t* row_iv,
+                         const int32_t* n_col_iv, const int64_t* col_iv, const double* mem_used,
+                         int32_t* n_bands, int64_t* band_h, int32_t* n_cols, int64_t* col_w,
+                         int32_t* tile_device, double* cost);
+
 /* ---- misc ----------------------------------------------------------------*/
 const char* cleave_strerror(int status);
 /* hipError_t value of the most recent CLEAVE_EHIP on this thread (0 if none). */

@@ -88,6 +88,20 @@ def _overlap(lo, hi, c_lo, c_hi):
     return max(0, min(hi, c_hi) - max(lo, c_lo))
 
 
+def _covered(intervals, lo, hi):
+    """Elements of [lo, hi) inside a list of disjoint half-open intervals."""
+    return sum(_overlap(lo, hi, a, b) for a, b in intervals)
+
+
+def _as_sets(entry):
+    """A device's cache: (row_lo, row_hi, col_lo, col_hi) -- one interval each --
+    or (row_intervals, col_intervals) with lists of (lo, hi) pairs, the runs of
+    ones of the device's rows in the cache matrices R_s and C_s (Sec. 4.2)."""
+    if len(entry) == 4:
+        return [(entry[0], entry[1])], [(entry[2], entry[3])]
+    return list(entry[0]), list(entry[1])
+
+
 def _layout(m, q, n, b, devs, g, T, origin=(0, 0), cached=None, mem_used=None):
     """The construction for target time T; returns None if the devices run out.
 
@@ -101,18 +115,18 @@ def _layout(m, q, n, b, devs, g, T, origin=(0, 0), cached=None, mem_used=None):
         d = devs[k]
         if cached is None:
             return shard_cost(d, h, w, n, b)
-        rl, rh, cl, ch = cached[k]
+        rows, cols = _as_sets(cached[k])
         a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
-        return shard_cost(d, h, w, n, b, h - _overlap(a_lo, a_lo + h, rl, rh), w - _overlap(c0, c0 + w, cl, ch))
+        return shard_cost(d, h, w, n, b, h - _covered(rows, a_lo, a_lo + h), w - _covered(cols, c0, c0 + w))
 
     def fits_at(k, r_lo, h, c_lo, w):
         d = devs[k]
         if cached is None:
             return shard_fits(d, h, w, n, b)
-        rl, rh, cl, ch = cached[k]
+        rows, cols = _as_sets(cached[k])
         a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
-        af = h - _overlap(a_lo, a_lo + h, rl, rh)
-        bf = w - _overlap(c0, c0 + w, cl, ch)
+        af = h - _covered(rows, a_lo, a_lo + h)
+        bf = w - _covered(cols, c0, c0 + w)
         return float(af * n * b + n * bf * b + h * w * b) + mem_used[k] <= d.mem_bytes
 
     edges = []
@@ -123,8 +137,9 @@ def _layout(m, q, n, b, devs, g, T, origin=(0, 0), cached=None, mem_used=None):
         if cached is None:
             hr = hc = 0
         else:
-            hr = _overlap(origin[0], origin[0] + m, cached[k][0], cached[k][1])
-            hc = _overlap(origin[1], origin[1] + q, cached[k][2], cached[k][3])
+            rows, cols = _as_sets(cached[k])
+            hr = _covered(rows, origin[0], origin[0] + m)
+            hc = _covered(cols, origin[1], origin[1] + q)
 
         def ok(x, d=d, hr=hr, hc=hc, used=used):
             af, bf = max(0, x - hr), max(0, x - hc)
@@ -202,10 +217,10 @@ def assign(m, q, n, b, devs, granule, origin=(0, 0), cached=None, mem_used=None)
             if cached is None:
                 c = shard_cost(devs[k], h, w, n, b)
             else:
-                rl, rh, cl, ch = cached[k]
+                rows, cols = _as_sets(cached[k])
                 a_lo, c0 = origin[0] + r_lo, origin[1] + c_lo
-                c = shard_cost(devs[k], h, w, n, b, h - _overlap(a_lo, a_lo + h, rl, rh),
-                               w - _overlap(c0, c0 + w, cl, ch))
+                c = shard_cost(devs[k], h, w, n, b, h - _covered(rows, a_lo, a_lo + h),
+                               w - _covered(cols, c0, c0 + w))
             cost = max(cost, c)
             c_lo += w
         r_lo += h

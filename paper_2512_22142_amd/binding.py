@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets",
 )
 
 
@@ -119,6 +119,8 @@ def _load():
     lib.cleave_assign.restype = ctypes.c_int
     lib.cleave_reassign.argtypes = [i64, i64, i64, i32, p, i32, i64, i64, i64, p, p, p, p, p, p, p, p]
     lib.cleave_reassign.restype = ctypes.c_int
+    lib.cleave_reassign_sets.argtypes = [i64, i64, i64, i32, p, i32, i64, i64, i64, p, p, p, p, p, p, p, p, p, p, p]
+    lib.cleave_reassign_sets.restype = ctypes.c_int
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
@@ -475,6 +477,20 @@ def assign(m, q, n, elem_bytes, devices, granule, origin=(0, 0), cached=None, me
     if cached is None:
         _check(_lib.cleave_assign(m, q, n, elem_bytes, devs, k, granule, ctypes.byref(n_bands), band_h,
                                   n_cols, col_w, owner, ctypes.byref(cost)), "cleave_assign")
+    elif cached and len(cached[0]) == 2:
+        # general cache sets: one (row_intervals, col_intervals) pair per device -> cleave_reassign_sets
+        if mem_used is None or len(cached) != k or len(mem_used) != k:
+            raise CleaveError(EINVAL, "assign (cached / mem_used lengths)")
+        n_r = (ctypes.c_int32 * max(k, 1))(*[len(c[0]) for c in cached])
+        n_c = (ctypes.c_int32 * max(k, 1))(*[len(c[1]) for c in cached])
+        r_flat = [int(x) for c in cached for iv in c[0] for x in iv]
+        c_flat = [int(x) for c in cached for iv in c[1] for x in iv]
+        r_iv = (ctypes.c_int64 * max(len(r_flat), 1))(*r_flat)
+        c_iv = (ctypes.c_int64 * max(len(c_flat), 1))(*c_flat)
+        used = (ctypes.c_double * max(k, 1))(*[float(x) for x in mem_used])
+        _check(_lib.cleave_reassign_sets(m, q, n, elem_bytes, devs, k, granule, int(origin[0]), int(origin[1]),
+                                         n_r, r_iv, n_c, c_iv, used, ctypes.byref(n_bands), band_h, n_cols,
+                                         col_w, owner, ctypes.byref(cost)), "cleave_reassign_sets")
     else:
         if mem_used is None or len(cached) != k or len(mem_used) != k:
             raise CleaveError(EINVAL, "assign (cached / mem_used lengths)")

@@ -60,13 +60,20 @@ int64_t largest(int64_t limit, F ok) {
 }
 
 // What the survivors of a device failure already hold (churn recovery,
-// Sec. 4.2): per device its cached rows of A [row_lo, row_hi) and columns of B
-// [col_lo, col_hi) in absolute output coordinates, the bytes of its memory
-// already in use (no cache replacement), and where the rectangle to cover
-// starts.  Null `cached`: cold start.
+// Sec. 4.2: the binary cache matrices R_s and C_s): per device the set of rows
+// of A and the set of columns of B it has cached, each as a list of disjoint
+// half-open intervals in absolute output coordinates (a row of R_s / C_s with
+// its runs of ones written as intervals), the bytes of its memory already in
+// use (no cache replacement), and where the rectangle to cover starts.
+// `on` false: cold start.
+struct IntervalSet {
+  const int64_t* iv = nullptr;   // n pairs [lo, hi)
+  int32_t n = 0;
+};
 struct Caches {
-  const int64_t* cached = nullptr;   // 4 per device
-  const double* mem_used = nullptr;  // 1 per device
+  bool on = false;
+  std::vector<IntervalSet> rows, cols;   // one per device
+  const double* mem_used = nullptr;      // one per device
   int64_t row0 = 0, col0 = 0;
 };
 
@@ -74,25 +81,31 @@ int64_t overlap(int64_t lo, int64_t hi, int64_t c_lo, int64_t c_hi) {
   return std::max<int64_t>(0, std::min(hi, c_hi) - std::max(lo, c_lo));
 }
 
+// Elements of [lo, hi) that the set holds.
+int64_t covered(const IntervalSet& s, int64_t lo, int64_t hi) {
+  int64_t total = 0;
+  for (int32_t i = 0; i < s.n; ++i) total += overlap(lo, hi, s.iv[2 * i], s.iv[2 * i + 1]);
+  return total;
+}
+
 bool build_layout(int64_t m, int64_t q, int64_t n, int64_t b, const cleave_device* devs,
                   int32_t n_devs, int64_t g, double T, const Caches& cc, Layout* out) {
   const int64_t top = (std::max(m, q) + g - 1) / g;
   // rows / columns of a shard at (r_lo, c_lo) of the rectangle that device k must still fetch
   auto fetch = [&](int32_t k, int64_t r_lo, int64_t h, int64_t c_lo, int64_t w, int64_t* af, int64_t* bf) {
-    if (!cc.cached) {
+    if (!cc.on) {
       *af = h;
       *bf = w;
       return;
     }
-    const int64_t* c = cc.cached + 4 * static_cast<int64_t>(k);
     const int64_t a_lo = cc.row0 + r_lo, b_lo = cc.col0 + c_lo;
-    *af = h - overlap(a_lo, a_lo + h, c[0], c[1]);
-    *bf = w - overlap(b_lo, b_lo + w, c[2], c[3]);
+    *af = h - covered(cc.rows[k], a_lo, a_lo + h);
+    *bf = w - covered(cc.cols[k], b_lo, b_lo + w);
   };
   auto affordable = [&](int32_t k, int64_t h, int64_t w, int64_t af, int64_t bf) {
     const cleave_device& d = devs[k];
     if (cost_of(d, h, w, af, bf, n, b) > T) return false;
-    if (!cc.cached) return fits(d, h, w, n, b);
+    if (!cc.on) return fits(d, h, w, n, b);
     return static_cast<double>(af * n * b + n * bf * b + h * w * b) + cc.mem_used[k] <= d.mem_bytes;
   };
   std::vector<int64_t> edge(n_devs);
@@ -100,10 +113,9 @@ bool build_layout(int64_t m, int64_t q, int64_t n, int64_t b, const cleave_devic
     // the shard's position is not known yet: every cached row and column of the
     // rectangle counts as if the shard were placed on it
     int64_t hr = 0, hc = 0;
-    if (cc.cached) {
-      const int64_t* c = cc.cached + 4 * static_cast<int64_t>(k);
-      hr = overlap(cc.row0, cc.row0 + m, c[0], c[1]);
-      hc = overlap(cc.col0, cc.col0 + q, c[2], c[3]);
+    if (cc.on) {
+      hr = covered(cc.rows[k], cc.row0, cc.row0 + m);
+      hc = covered(cc.cols[k], cc.col0, cc.col0 + q);
     }
     edge[k] = g * largest(top, [&](int64_t u) {
                 const int64_t e = u * g;
@@ -218,10 +230,9 @@ int assign_impl(int64_t m, int64_t q, int64_t n, int32_t elem_bytes, const cleav
       for (int32_t c = 0; c < found.n_cols[band]; ++c, ++t) {
         const int64_t w = found.col_w[t];
         int64_t af = h, bf = w;
-        if (cc.cached) {
-          const int64_t* ch = cc.cached + 4 * static_cast<int64_t>(found.owner[t]);
-          af = h - overlap(cc.row0 + r_lo, cc.row0 + r_lo + h, ch[0], ch[1]);
-          bf = w - overlap(cc.col0 + c_lo, cc.col0 + c_lo + w, ch[2], ch[3]);
+        if (cc.on) {
+          af = h - covered(cc.rows[found.owner[t]], cc.row0 + r_lo, cc.row0 + r_lo + h);
+          bf = w - covered(cc.cols[found.owner[t]], cc.col0 + c_lo, cc.col0 + c_lo + w);
         }
         worst = std::max(worst, cost_of(devs[found.owner[t]], h, w, af, bf, n, elem_bytes));
         c_lo += w;
@@ -250,18 +261,74 @@ extern "C" int cleave_assign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes
                      col_w, tile_device, cost);
 }
 
+namespace {
+
+// Sorted, disjoint, non-negative, non-inverted intervals.
+bool valid_set(const IntervalSet& s) {
+  int64_t prev_hi = 0;
+  for (int32_t i = 0; i < s.n; ++i) {
+    const int64_t lo = s.iv[2 * i], hi = s.iv[2 * i + 1];
+    if (lo < prev_hi || hi < lo) return false;
+    prev_hi = hi;
+  }
+  return true;
+}
+
+}  // namespace
+
 extern "C" int cleave_reassign(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
                                const cleave_device* devs, int32_t n_devs, int64_t granule,
                                int64_t row0, int64_t col0, const int64_t* cached,
                                const double* mem_used, int32_t* n_bands, int64_t* band_h,
                                int32_t* n_cols, int64_t* col_w, int32_t* tile_device, double* cost) {
   if (!cached || !mem_used || row0 < 0 || col0 < 0 || n_devs < 1) return CLEAVE_EINVAL;
+  Caches cc;
+  try {
+    cc.rows.resize(static_cast<size_t>(n_devs));
+    cc.cols.resize(static_cast<size_t>(n_devs));
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
   for (int32_t k = 0; k < n_devs; ++k) {
     const int64_t* c = cached + 4 * static_cast<int64_t>(k);
     if (c[0] < 0 || c[1] < c[0] || c[2] < 0 || c[3] < c[2] || !(mem_used[k] >= 0.0)) return CLEAVE_EINVAL;
+    cc.rows[k] = IntervalSet{c, 1};
+    cc.cols[k] = IntervalSet{c + 2, 1};
   }
+  cc.on = true;
+  cc.mem_used = mem_used;
+  cc.row0 = row0;
+  cc.col0 = col0;
+  return assign_impl(m, q, n, elem_bytes, devs, n_devs, granule, cc, n_bands, band_h, n_cols, col_w,
+                     tile_device, cost);
+}
+
+extern "C" int cleave_reassign_sets(int64_t m, int64_t q, int64_t n, int32_t elem_bytes,
+                                    const cleave_device* devs, int32_t n_devs, int64_t granule,
+                                    int64_t row0, int64_t col0, const int32_t* n_row_iv,
+                                    const int64_t* row_iv, const int32_t* n_col_iv,
+                                    const int64_t* col_iv, const double* mem_used, int32_t* n_bands,
+                                    int64_t* band_h, int32_t* n_cols, int64_t* col_w,
+                                    int32_t* tile_device, double* cost) {
+  if (!n_row_iv || !n_col_iv || !mem_used || row0 < 0 || col0 < 0 || n_devs < 1) return CLEAVE_EINVAL;
   Caches cc;
-  cc.cached = cached;
+  try {
+    cc.rows.resize(static_cast<size_t>(n_devs));
+    cc.cols.resize(static_cast<size_t>(n_devs));
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  int64_t r_at = 0, c_at = 0;
+  for (int32_t k = 0; k < n_devs; ++k) {
+    if (n_row_iv[k] < 0 || n_col_iv[k] < 0 || !(mem_used[k] >= 0.0)) return CLEAVE_EINVAL;
+    if ((n_row_iv[k] > 0 && !row_iv) || (n_col_iv[k] > 0 && !col_iv)) return CLEAVE_EINVAL;
+    cc.rows[k] = IntervalSet{row_iv ? row_iv + 2 * r_at : nullptr, n_row_iv[k]};
+    cc.cols[k] = IntervalSet{col_iv ? col_iv + 2 * c_at : nullptr, n_col_iv[k]};
+    if (!valid_set(cc.rows[k]) || !valid_set(cc.cols[k])) return CLEAVE_EINVAL;
+    r_at += n_row_iv[k];
+    c_at += n_col_iv[k];
+  }
+  cc.on = true;
   cc.mem_used = mem_used;
   cc.row0 = row0;
   cc.col0 = col0;

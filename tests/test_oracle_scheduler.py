@@ -104,7 +104,8 @@ def test_against_brute_force_on_tiny_instances(seed):
     check_layout(m, q, n, b, devs, g, res)
     opt = brute_force_optimum(m, q, n, b, devs, g)
     assert res[3] >= opt * (1 - 1e-12)          # nothing beats the enumerated optimum
-    assert res[3] <= 2.0 * opt                  # and the heuristic stays within a factor two of it here
+    assert res[3] <= 1.15 * opt                 # the heuristic stays close to it (observed <= 1.08 on these and on
+                                                # the 30 larger instances of test_scheduler_independent.py)
 
 
 def test_stronger_device_gets_the_larger_shard_and_weak_ones_may_idle():
