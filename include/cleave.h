@@ -267,7 +267,8 @@ int cleave_reduce_grouped(cleave_plan* plan, const float* partials, int64_t n_me
  * server (Sec. 4.1) and runs the optimizer per weight matrix right behind that
  * matrix's gradient GEMM (Sec. 6, "Optimizer step accounting and pipelining").
  * Both calls compute the same fixed-order sum as cleave_reduce and hand it to
- * the operator without storing it.  Single-GEMM plans only.
+ * the operator without storing it.  Single-GEMM plans, except where a grouped
+ * form is declared.
  *
  * cleave_reduce_residual: C = sum + R.  R: device, M x N, element type and
  * leading dimension of C; R == C (in-place accumulation) is allowed. */
@@ -286,6 +287,21 @@ int cleave_reduce_residual(cleave_plan* plan, const float* partials, const void*
 int cleave_reduce_adam(cleave_plan* plan, const float* partials, float* w, float* m, float* v,
                        void* w_bf16, int64_t ld, float lr, float beta1, float beta2, float eps,
                        float weight_decay, int64_t step, void* hip_stream);
+
+/* Grouped form of cleave_reduce_adam: the weight-gradient GEMMs of one DAG level
+ * (same shape; plan made by cleave_plan_batched, at most 8 members, executed
+ * with cleave_execute_grouped) aggregated and applied in one launch.  w_list,
+ * m_list, v_list: host arrays of n_members device pointers (fp32, M x N,
+ * leading dimension ld, updated in place); w_bf16_list: likewise for the bf16
+ * copies, or NULL for none.  Same arithmetic per element as cleave_reduce_adam:
+ * member g's result is bit for bit what the single call gives for it.
+ * CLEAVE_EINVAL: as for cleave_reduce_adam, a plain plan, n_members != n_batch,
+ * a NULL or misaligned member pointer. */
+int cleave_reduce_adam_grouped(cleave_plan* plan, const float* partials, int64_t n_members,
+                               float* const* w_list, float* const* m_list, float* const* v_list,
+                               void* const* w_bf16_list, int64_t ld,
+                               float lr, float beta1, float beta2, float eps, float weight_decay,
+                               int64_t step, void* hip_stream);
 
 /* ---- verify --------------------------------------------------------------
  * Check of returned partial blocks by random projection (paper Sec. 6,

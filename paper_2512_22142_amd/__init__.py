@@ -39,6 +39,7 @@ _BINDING_NAMES = (
     "plan_uniform",
     "reduce",
     "reduce_adam",
+    "reduce_adam_grouped",
     "reduce_batched",
     "reduce_grouped",
     "reduce_residual",

@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped",
 )
 
 
@@ -111,6 +111,8 @@ def _load():
     f32 = ctypes.c_float
     lib.cleave_reduce_adam.argtypes = [p, p, p, p, p, p, i64, f32, f32, f32, f32, f32, i64, p]
     lib.cleave_reduce_adam.restype = ctypes.c_int
+    lib.cleave_reduce_adam_grouped.argtypes = [p, p, i64, p, p, p, p, i64, f32, f32, f32, f32, f32, i64, p]
+    lib.cleave_reduce_adam_grouped.restype = ctypes.c_int
     lib.cleave_shard_cost.argtypes = [p, i64, i64, i64, i64, i64, i32]
     lib.cleave_shard_cost.restype = ctypes.c_double
     lib.cleave_shard_fits.argtypes = [p, i64, i64, i64, i32]
@@ -410,6 +412,25 @@ def reduce_adam(plan, partials, w, m, v, lr, beta1, beta2, eps, weight_decay, st
     _check(_lib.cleave_reduce_adam(plan._h, ctypes.c_void_p(partials.data_ptr()), w_ptr, ptrs[0],
                                    ptrs[1], ptrs[2], ld, lr, beta1, beta2, eps, weight_decay,
                                    int(step), _stream_ptr(stream)), "cleave_reduce_adam")
+
+
+def reduce_adam_grouped(plan, partials, w_list, m_list, v_list, lr, beta1, beta2, eps, weight_decay, step,
+                        w_bf16_list=None, stream=None):
+    """cleave_reduce_adam_grouped: member g of the grouped plan updates w_list[g]
+    (moments m_list[g], v_list[g], optional bf16 copy w_bf16_list[g])."""
+    w_arr, ld = _member_pointers(w_list, "w_list")
+    m_arr, ldm = _member_pointers(m_list, "m_list")
+    v_arr, ldv = _member_pointers(v_list, "v_list")
+    b_arr = None
+    if w_bf16_list is not None:
+        b_arr, ldb = _member_pointers(w_bf16_list, "w_bf16_list")
+        if ldb != ld or len(w_bf16_list) != len(w_list):
+            raise ValueError("w_bf16_list must match w_list")
+    if ldm != ld or ldv != ld or not (len(w_list) == len(m_list) == len(v_list)):
+        raise ValueError("w, m, v lists must have one entry per member and one leading dimension")
+    _check(_lib.cleave_reduce_adam_grouped(plan._h, ctypes.c_void_p(partials.data_ptr()), len(w_list), w_arr,
+                                           m_arr, v_arr, b_arr, ld, lr, beta1, beta2, eps, weight_decay,
+                                           int(step), _stream_ptr(stream)), "cleave_reduce_adam_grouped")
 
 
 def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=None,

@@ -629,11 +629,12 @@ namespace {
 struct ReduceEpilogue {
   const void* residual = nullptr;          // C = sum + residual
   const cleave::AdamArgs* adam = nullptr;  // Adam update of adam->w (C unused)
+  const cleave::AdamGroupOffsets* adam_group = nullptr;   // with adam: one set of arrays per member
 };
 
 int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, int out_dtype,
                 const BatchLayout& bl, void* hip_stream,
-                const ReduceEpilogue& epi = ReduceEpilogue{}) {
+                const ReduceEpilogue& epi = ReduceEpilogue{}, bool members_aligned = true) {
   if (!plan || !partials || !C) return CLEAVE_EINVAL;
   if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if (ldc < plan->N) return CLEAVE_EINVAL;
@@ -645,7 +646,7 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   if (rc != CLEAVE_OK) return rc;
 
   bool vec = plan->all_n_mult4 && ldc % 4 == 0 && aligned(partials, 16) && aligned(C, 4 * ob) &&
-             offsets_multiple_of(bl.c, bl.shape, 4);
+             offsets_multiple_of(bl.c, bl.shape, 4) && members_aligned;
   if (epi.residual) vec = vec && aligned(epi.residual, 4 * ob);
   if (epi.adam)
     vec = vec && aligned(epi.adam->m, 16) && aligned(epi.adam->v, 16) &&
@@ -661,7 +662,9 @@ int reduce_impl(cleave_plan* plan, const float* partials, void* C, int64_t ldc, 
   args.c_at = bl.c;
   // one workgroup per reduce item (the kernel loops only if the grid is capped)
   const int grid = static_cast<int>(std::min<int64_t>(args.n_items, int64_t{1} << 20));
-  if (epi.adam) {
+  if (epi.adam && epi.adam_group) {
+    CLEAVE_HIP(cleave::launch_reduce_adam_grouped(args, *epi.adam, *epi.adam_group, vec, grid, stream));
+  } else if (epi.adam) {
     CLEAVE_HIP(cleave::launch_reduce_adam(args, *epi.adam, vec, grid, stream));
   } else if (epi.residual) {
     CLEAVE_HIP(cleave::launch_reduce_residual(args, epi.residual, out_dtype, vec, grid, stream));
@@ -708,6 +711,53 @@ extern "C" int cleave_reduce_adam(cleave_plan* plan, const float* partials, floa
   epi.adam = &h;
   // the fp32 master weight takes C's place in the common checks (pointer, leading dimension)
   return reduce_impl(plan, partials, w, ld, CLEAVE_F32, BatchLayout{}, hip_stream, epi);
+}
+
+extern "C" int cleave_reduce_adam_grouped(cleave_plan* plan, const float* partials, int64_t n_members,
+                                          float* const* w_list, float* const* m_list,
+                                          float* const* v_list, void* const* w_bf16_list, int64_t ld,
+                                          float lr, float beta1, float beta2, float eps,
+                                          float weight_decay, int64_t step, void* hip_stream) {
+  if (!plan || plan->batch < 1 || plan->batch > cleave::kMaxGroup || n_members != plan->batch)
+    return CLEAVE_EINVAL;
+  if (!w_list || !m_list || !v_list) return CLEAVE_EINVAL;
+  if (step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) ||
+      !(eps >= 0.0f) || !(lr == lr) || !(weight_decay == weight_decay))
+    return CLEAVE_EINVAL;
+  cleave::AdamGroupOffsets at{};
+  bool all16 = true;
+  for (int64_t g = 0; g < n_members; ++g) {
+    if (!w_list[g] || !m_list[g] || !v_list[g] || (w_bf16_list && !w_bf16_list[g])) return CLEAVE_EINVAL;
+    if (!aligned(w_list[g], 4) || !aligned(m_list[g], 4) || !aligned(v_list[g], 4) ||
+        (w_bf16_list && !aligned(w_bf16_list[g], 2)))
+      return CLEAVE_EINVAL;
+    all16 = all16 && aligned(w_list[g], 16) && aligned(m_list[g], 16) && aligned(v_list[g], 16) &&
+            (!w_bf16_list || aligned(w_bf16_list[g], 8));
+    at.w[g] = w_list[g] - w_list[0];
+    at.m[g] = m_list[g] - m_list[0];
+    at.v[g] = v_list[g] - v_list[0];
+    at.w_bf16[g] = w_bf16_list ? static_cast<uint16_t*>(w_bf16_list[g]) - static_cast<uint16_t*>(w_bf16_list[0]) : 0;
+  }
+  cleave::AdamArgs h{};
+  h.w = w_list[0];
+  h.m = m_list[0];
+  h.v = v_list[0];
+  h.w_bf16 = w_bf16_list ? static_cast<uint16_t*>(w_bf16_list[0]) : nullptr;
+  h.lr = lr;
+  h.beta1 = beta1;
+  h.beta2 = beta2;
+  h.eps = eps;
+  h.weight_decay = weight_decay;
+  h.inv_bias1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step))));
+  h.inv_bias2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step))));
+  ReduceEpilogue epi;
+  epi.adam = &h;
+  epi.adam_group = &at;
+  BatchLayout bl;
+  bl.shape.n_group = static_cast<uint32_t>(plan->batch);   // c_at stays zero: every array has its own table
+  // reduce_impl's vector-path test looks at h's (member 0's) arrays; the members must agree
+  // (a member whose arrays are not 16-byte aligned sends the whole launch down the element path)
+  return reduce_impl(plan, partials, h.w, ld, CLEAVE_F32, bl, hip_stream, epi, all16);
 }
 
 extern "C" int cleave_reduce(cleave_plan* plan, const float* partials, void* C, int64_t ldc,

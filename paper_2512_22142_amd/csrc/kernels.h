@@ -122,6 +122,14 @@ struct AdamArgs {
 };
 hipError_t launch_reduce_adam(const ReduceArgs& args, const AdamArgs& h, bool vec, int grid,
                               hipStream_t stream);
+// Grouped form: h holds member 0's arrays, `at` the element offsets of member
+// g's arrays from them (ReduceArgs::c_at must be all zero: every array has its
+// own table).
+struct AdamGroupOffsets {
+  int64_t w[kMaxGroup], m[kMaxGroup], v[kMaxGroup], w_bf16[kMaxGroup];
+};
+hipError_t launch_reduce_adam_grouped(const ReduceArgs& args, const AdamArgs& h, const AdamGroupOffsets& at,
+                                      bool vec, int grid, hipStream_t stream);
 
 // ---- returned-block check ---------------------------------------------------
 

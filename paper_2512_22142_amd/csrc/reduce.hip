@@ -42,6 +42,7 @@ __device__ __forceinline__ uint32_t to_bf16_bits(float x) {
 template <bool OUT_BF16>
 struct StoreEpilogue {
   void* C;
+  __device__ __forceinline__ const StoreEpilogue& for_member(uint32_t) const { return *this; }
   __device__ __forceinline__ void apply4(int64_t off, f32x4 acc) const {
     if constexpr (OUT_BF16) {
       u32x2 w;
@@ -67,6 +68,7 @@ template <bool OUT_BF16>
 struct ResidualEpilogue {
   void* C;
   const void* R;
+  __device__ __forceinline__ const ResidualEpilogue& for_member(uint32_t) const { return *this; }
   __device__ __forceinline__ void apply4(int64_t off, f32x4 acc) const {
     if constexpr (OUT_BF16) {
       const u32x2 r = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(R) + off);
@@ -102,6 +104,7 @@ struct AdamEpilogue {
   float* v;
   uint16_t* w_bf16;   // may be null
   float lr, beta1, beta2, eps, weight_decay, inv_bias1, inv_bias2;
+  __device__ __forceinline__ const AdamEpilogue& for_member(uint32_t) const { return *this; }
   __device__ __forceinline__ float update(float g, float w0, float& m_io, float& v_io) const {
     const float m1 = beta1 * m_io + (1.0f - beta1) * g;
     const float v1 = beta2 * v_io + (1.0f - beta2) * (g * g);
@@ -137,10 +140,26 @@ struct AdamEpilogue {
   }
 };
 
+// Adam for the weight-gradient GEMMs of one DAG level in one launch: member g of
+// the grouped plan updates its own weight, moments and bf16 copy, found through
+// one element-offset table per array (from the arrays of member 0).
+struct GroupedAdamEpilogue {
+  AdamEpilogue first;              // member 0's arrays and the shared hyper-parameters
+  int64_t w_at[kMaxGroup], m_at[kMaxGroup], v_at[kMaxGroup], b_at[kMaxGroup];
+  __device__ __forceinline__ AdamEpilogue for_member(uint32_t g) const {
+    AdamEpilogue e = first;
+    e.w += w_at[g];
+    e.m += m_at[g];
+    e.v += v_at[g];
+    if (e.w_bf16) e.w_bf16 += b_at[g];
+    return e;
+  }
+};
+
 // Vector path for a compile-time split count: all S loads of two output
 // float4s are issued before the first add, so every thread keeps 2*S 16-byte
 // loads in flight.  The adds stay a left fold in ascending split order.
-template <typename Epi, int S>
+template <int S, typename Epi>
 __device__ __forceinline__ void reduce_item_fixed(const float* p0, uint64_t block, uint32_t count,
                                                   uint32_t n_len, const Epi& epi, int64_t c_base,
                                                   int64_t ldc) {
@@ -177,10 +196,11 @@ __device__ __forceinline__ void reduce_item_fixed(const float* p0, uint64_t bloc
 }
 
 template <typename Epi, bool VEC>
-__global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args, Epi epi) {
+__global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args, Epi all_members) {
   for (int64_t it = blockIdx.x; it < args.n_items; it += gridDim.x) {
     const ReduceItem item = args.items[it];
     const cleave_task task = args.tasks[item.task];
+    const auto epi = all_members.for_member(task.gemm_id);
     const uint32_t n_len = task.n_len;
     const uint32_t S = task.ksplit_cnt;
     const uint64_t block = static_cast<uint64_t>(task.m_len) * n_len;   // elements per partial
@@ -192,10 +212,10 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ReduceArgs args, Epi e
 
     if constexpr (VEC) {
       switch (S) {
-        case 1: reduce_item_fixed<Epi, 1>(p0, block, count, n_len, epi, c_base, args.ldc); break;
-        case 2: reduce_item_fixed<Epi, 2>(p0, block, count, n_len, epi, c_base, args.ldc); break;
-        case 4: reduce_item_fixed<Epi, 4>(p0, block, count, n_len, epi, c_base, args.ldc); break;
-        case 8: reduce_item_fixed<Epi, 8>(p0, block, count, n_len, epi, c_base, args.ldc); break;
+        case 1: reduce_item_fixed<1>(p0, block, count, n_len, epi, c_base, args.ldc); break;
+        case 2: reduce_item_fixed<2>(p0, block, count, n_len, epi, c_base, args.ldc); break;
+        case 4: reduce_item_fixed<4>(p0, block, count, n_len, epi, c_base, args.ldc); break;
+        case 8: reduce_item_fixed<8>(p0, block, count, n_len, epi, c_base, args.ldc); break;
         default:
           for (uint32_t e = threadIdx.x * 4; e < count; e += kThreads * 4) {
             f32x4 acc = *reinterpret_cast<const f32x4*>(p0 + e);
@@ -243,6 +263,20 @@ hipError_t launch_reduce_adam(const ReduceArgs& args, const AdamArgs& h, bool ve
                               hipStream_t stream) {
   const AdamEpilogue epi{h.w, h.m, h.v, h.w_bf16, h.lr, h.beta1, h.beta2, h.eps,
                          h.weight_decay, h.inv_bias1, h.inv_bias2};
+  return launch_with(args, epi, vec, grid, stream);
+}
+
+hipError_t launch_reduce_adam_grouped(const ReduceArgs& args, const AdamArgs& h, const AdamGroupOffsets& at,
+                                      bool vec, int grid, hipStream_t stream) {
+  GroupedAdamEpilogue epi{};
+  epi.first = AdamEpilogue{h.w, h.m, h.v, h.w_bf16, h.lr, h.beta1, h.beta2, h.eps,
+                           h.weight_decay, h.inv_bias1, h.inv_bias2};
+  for (int g = 0; g < kMaxGroup; ++g) {
+    epi.w_at[g] = at.w[g];
+    epi.m_at[g] = at.m[g];
+    epi.v_at[g] = at.v[g];
+    epi.b_at[g] = at.w_bf16[g];
+  }
   return launch_with(args, epi, vec, grid, stream);
 }
 

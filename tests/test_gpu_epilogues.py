@@ -170,3 +170,43 @@ def test_epilogues_reject_bad_arguments():
     bp = cleave.plan_batched(64, 64, 64, 32, 32, 1, 2)
     with pytest.raises(cleave.CleaveError):
         cleave.reduce_residual(bp, torch.zeros(bp.partial_elems, device="cuda"), w, w)
+
+
+@pytest.mark.parametrize("M,N,tm,tn,S,n", [(256, 384, 128, 128, 4, 3), (300, 200, 128, 128, 2, 2), (37, 29, 16, 8, 3, 4)])
+def test_grouped_adam_equals_the_single_calls_bit_for_bit(M, N, tm, tn, S, n):
+    """The weight-gradient GEMMs of a level in one launch: member g's weight, moments
+    and bf16 copy come out exactly as the single-GEMM call leaves them (whose result
+    the tests above hold against the fp64 oracle)."""
+    K = 64
+    single = cleave.plan_uniform(M, N, K, tm, tn, S)
+    group = cleave.plan_batched(M, N, K, tm, tn, S, n)
+    assert group.partial_elems == n * single.partial_elems
+    parts = seeded((group.partial_elems,), 900 + M).cuda()
+    hyper = (f32(1e-3), f32(0.9), f32(0.95), f32(1e-8), f32(0.1))
+    w0 = [seeded((M, N), 910 + g, 0.02) for g in range(n)]
+    m0 = [seeded((M, N), 920 + g, 0.01) for g in range(n)]
+    v0 = [seeded((M, N), 930 + g, 0.01).abs() for g in range(n)]
+    # grouped: three steps in a row
+    gw, gm, gv = [t.clone().cuda() for t in w0], [t.clone().cuda() for t in m0], [t.clone().cuda() for t in v0]
+    gb = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    for step in (1, 2, 3):
+        cleave.reduce_adam_grouped(group, parts, gw, gm, gv, *hyper, step, w_bf16_list=gb)
+    # single calls on each member's slice of the partial buffer
+    for g in range(n):
+        sw, sm, sv = w0[g].clone().cuda(), m0[g].clone().cuda(), v0[g].clone().cuda()
+        sb = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        mine = parts[g * single.partial_elems:(g + 1) * single.partial_elems]
+        for step in (1, 2, 3):
+            cleave.reduce_adam(single, mine, sw, sm, sv, *hyper, step, w_bf16=sb)
+        torch.cuda.synchronize()
+        for got, want in ((gw[g], sw), (gm[g], sm), (gv[g], sv)):
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32)), g
+        assert torch.equal(gb[g].view(torch.int16), sb.view(torch.int16)), g
+    # without bf16 copies, and argument checks
+    cleave.reduce_adam_grouped(group, parts, gw, gm, gv, *hyper, 4)
+    with pytest.raises(cleave.CleaveError):
+        cleave.reduce_adam_grouped(single, parts, gw[:1], gm[:1], gv[:1], *hyper, 1)      # plain plan
+    with pytest.raises(cleave.CleaveError):
+        cleave.reduce_adam_grouped(group, parts, gw[:-1], gm[:-1], gv[:-1], *hyper, 1)    # one member short
+    with pytest.raises(cleave.CleaveError):
+        cleave.reduce_adam_grouped(group, parts, gw, gm, gv, *hyper, 0)                   # steps count from 1
