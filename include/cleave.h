@@ -324,13 +324,37 @@ int cleave_reduce_adam_grouped(cleave_plan* plan, const float* partials, int64_t
  * the operands per distinct row / column range of the tiling, per-item sums);
  * two verify calls on one plan must not overlap in time.
  * CLEAVE_EINVAL: NULL or misaligned pointer, bad enum, short leading
- * dimension, negative or NaN tol, or a batched plan. */
+ * dimension, negative or NaN tol, or a batched plan (use the forms below). */
 int cleave_verify(cleave_plan* plan,
                   const void* A, int64_t lda, int transA,
                   const void* B, int64_t ldb, int transB, int dtype,
                   const float* partials, const float* r, const float* s, double tol,
                   double* lhs, double* rhs, double* scale, int32_t* accept,
                   void* hip_stream);
+
+/* The same check for a plan made by cleave_plan_batched (the attention
+ * products of Sec. 3.1's table, or the same-shape GEMMs of a DAG level): every
+ * task of every member is checked against that member's operands.  Members are
+ * addressed as in cleave_execute_batched (strides) or cleave_execute_grouped
+ * (one pointer per member, at most 8).  r: n_batch x M floats, member g's probe
+ * vector at r + g * M; s: n_batch x N floats likewise; lhs, rhs, scale, accept:
+ * one entry per task of the batched task list.  Everything else, including the
+ * scratch the first call allocates and the rule that verify calls on one plan
+ * must not overlap, as for cleave_verify.  CLEAVE_EINVAL as for cleave_verify
+ * and the corresponding execute call, or a plain plan. */
+int cleave_verify_batched(cleave_plan* plan,
+                          const void* A, int64_t lda, int transA, int64_t a_outer, int64_t a_inner,
+                          const void* B, int64_t ldb, int transB, int64_t b_outer, int64_t b_inner,
+                          int64_t n_inner, int dtype,
+                          const float* partials, const float* r, const float* s, double tol,
+                          double* lhs, double* rhs, double* scale, int32_t* accept,
+                          void* hip_stream);
+int cleave_verify_grouped(cleave_plan* plan, int64_t n_members,
+                          const void* const* A_list, int64_t lda, int transA,
+                          const void* const* B_list, int64_t ldb, int transB, int dtype,
+                          const float* partials, const float* r, const float* s, double tol,
+                          double* lhs, double* rhs, double* scale, int32_t* accept,
+                          void* hip_stream);
 
 /* ---- cost model and shard assignment (host only) -------------------------
  * Paper Sec. 4.1: a device d receives alpha rows of A (m x n) and beta columns

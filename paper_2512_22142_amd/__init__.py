@@ -44,6 +44,8 @@ _BINDING_NAMES = (
     "reduce_grouped",
     "reduce_residual",
     "verify",
+    "verify_batched",
+    "verify_grouped",
     "version",
 )
 

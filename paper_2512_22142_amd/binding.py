@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped", "cleave_verify_batched", "cleave_verify_grouped",
 )
 
 
@@ -126,6 +126,12 @@ def _load():
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
+    lib.cleave_verify_batched.argtypes = [p, p, i64, ctypes.c_int, i64, i64, p, i64, ctypes.c_int, i64, i64, i64,
+                                          ctypes.c_int, p, p, p, ctypes.c_double, p, p, p, p, p]
+    lib.cleave_verify_batched.restype = ctypes.c_int
+    lib.cleave_verify_grouped.argtypes = [p, i64, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
+                                          p, p, p, ctypes.c_double, p, p, p, p, p]
+    lib.cleave_verify_grouped.restype = ctypes.c_int
     lib.cleave_reduce.restype = ctypes.c_int
     lib.cleave_strerror.argtypes = [ctypes.c_int]
     lib.cleave_strerror.restype = ctypes.c_char_p
@@ -463,6 +469,54 @@ def verify(plan, A, B, partials, r, s, tol, accept, lhs=None, rhs=None, scale=No
         vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
         vec(scale, torch.float64, plan.num_tasks, "scale", True),
         vec(accept, torch.int32, plan.num_tasks, "accept"), _stream_ptr(stream)), "cleave_verify")
+
+
+def _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale):
+    """Pointers of the verify calls' vector arguments for a batched plan (r, s
+    hold one probe vector per member)."""
+    import torch
+
+    def vec(t, dtype, n, what, optional=False):
+        if t is None and optional:
+            return None
+        if t is None or t.dtype != dtype or not t.is_cuda or not t.is_contiguous() or t.numel() < n:
+            raise ValueError("%s must be a contiguous %s device tensor of at least %d entries" % (what, dtype, n))
+        return ctypes.c_void_p(t.data_ptr())
+    members = r.numel() // plan.M
+    return (vec(partials, torch.float32, plan.partial_elems, "partials"),
+            vec(r, torch.float32, members * plan.M, "r"), vec(s, torch.float32, members * plan.N, "s"),
+            vec(lhs, torch.float64, plan.num_tasks, "lhs", True),
+            vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
+            vec(scale, torch.float64, plan.num_tasks, "scale", True),
+            vec(accept, torch.int32, plan.num_tasks, "accept"))
+
+
+def verify_batched(plan, A, a_strides, B, b_strides, n_inner, partials, r, s, tol, accept, lhs=None, rhs=None,
+                   scale=None, transA=0, transB=0, stream=None):
+    """cleave_verify_batched: members addressed as in execute_batched; r is
+    [n_batch, M], s is [n_batch, N] (fp32 device tensors)."""
+    a_ptr, lda = _device_2d(A, "A")
+    b_ptr, ldb = _device_2d(B, "B")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    pp, rp, sp, lp, hp, cp, ap = _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale)
+    _check(_lib.cleave_verify_batched(plan._h, a_ptr, lda, int(transA), int(a_strides[0]), int(a_strides[1]),
+                                      b_ptr, ldb, int(transB), int(b_strides[0]), int(b_strides[1]), int(n_inner),
+                                      _dtype_code(A), pp, rp, sp, float(tol), lp, hp, cp, ap, _stream_ptr(stream)),
+           "cleave_verify_batched")
+
+
+def verify_grouped(plan, A_list, B_list, partials, r, s, tol, accept, lhs=None, rhs=None, scale=None,
+                   transA=0, transB=0, stream=None):
+    """cleave_verify_grouped: one operand pair per member (as execute_grouped)."""
+    a_arr, lda = _member_pointers(A_list, "A_list")
+    b_arr, ldb = _member_pointers(B_list, "B_list")
+    if A_list[0].dtype != B_list[0].dtype or len(A_list) != len(B_list):
+        raise TypeError("A_list and B_list: one entry per member, one dtype")
+    pp, rp, sp, lp, hp, cp, ap = _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale)
+    _check(_lib.cleave_verify_grouped(plan._h, len(A_list), a_arr, lda, int(transA), b_arr, ldb, int(transB),
+                                      _dtype_code(A_list[0]), pp, rp, sp, float(tol), lp, hp, cp, ap,
+                                      _stream_ptr(stream)), "cleave_verify_grouped")
 
 
 def shard_cost(dev, alpha, beta, n, elem_bytes, alpha_fetch=None, beta_fetch=None):

@@ -842,7 +842,8 @@ int ensure_verify_tables(cleave_plan* p) {
   if (rc == CLEAVE_OK) rc = upload_vector(v->task_first_item, &v->d_task_first_item);
   if (rc == CLEAVE_OK) rc = upload_vector(v->items, &v->d_items);
   if (rc == CLEAVE_OK) {
-    const size_t proj = 2 * (v->row_segs.size() + v->col_segs.size()) * static_cast<size_t>(p->K);
+    const size_t members = p->batch > 0 ? static_cast<size_t>(p->batch) : 1;
+    const size_t proj = 2 * (v->row_segs.size() + v->col_segs.size()) * static_cast<size_t>(p->K) * members;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&v->d_proj), proj * sizeof(double));
     if (e == hipSuccess)
       e = hipMalloc(reinterpret_cast<void**>(&v->d_item_sums), v->items.size() * sizeof(double));
@@ -855,13 +856,13 @@ int ensure_verify_tables(cleave_plan* p) {
 
 }  // namespace
 
-extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int transA,
-                             const void* B, int64_t ldb, int transB, int dtype,
-                             const float* partials, const float* r, const float* s, double tol,
-                             double* lhs, double* rhs, double* scale, int32_t* accept,
-                             void* hip_stream) {
+namespace {
+
+int verify_impl(cleave_plan* plan, const void* A, int64_t lda, int transA, const void* B, int64_t ldb,
+                int transB, int dtype, const float* partials, const float* r, const float* s, double tol,
+                double* lhs, double* rhs, double* scale, int32_t* accept, const BatchLayout& bl,
+                void* hip_stream) {
   if (!plan || !A || !B || !partials || !r || !s || !accept) return CLEAVE_EINVAL;
-  if (plan->batch > 0) return CLEAVE_EINVAL;   // single-GEMM plans only
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
   if (lda < (transA ? plan->M : plan->K) || ldb < (transB ? plan->K : plan->N)) return CLEAVE_EINVAL;
@@ -881,12 +882,16 @@ extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int 
   if (plan->tasks.empty()) return CLEAVE_OK;
 
   const int64_t K = plan->K;
+  const bool batched = plan->batch > 0;
+  const int n_members = batched ? static_cast<int>(plan->batch) : 1;
   const int e = 16 / eb;   // elements per 16-byte load
   const bool segs_ok = e == 8 ? v->segs_mult8 : v->segs_mult4;
+  const size_t row_proj = v->row_segs.size() * static_cast<size_t>(K) * static_cast<size_t>(n_members);
+  const size_t col_proj = v->col_segs.size() * static_cast<size_t>(K) * static_cast<size_t>(n_members);
   double* U = v->d_proj;
-  double* U_abs = U + v->row_segs.size() * static_cast<size_t>(K);
-  double* V = U_abs + v->row_segs.size() * static_cast<size_t>(K);
-  double* V_abs = V + v->col_segs.size() * static_cast<size_t>(K);
+  double* U_abs = U + row_proj;
+  double* V = U_abs + row_proj;
+  double* V_abs = V + col_proj;
 
   // op(A)[i][k]: stored M x K (transA = 0) -> the summed row index strides;
   // stored K x M (transA = 1) -> it is contiguous.  op(B)[k][j]: stored K x N
@@ -894,21 +899,74 @@ extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int 
   // strides.
   const bool a_contig = transA != 0;
   const bool b_contig = transB == 0;
-  const bool a_vec = aligned(A, 16) && lda % e == 0 &&
-                     (a_contig ? (segs_ok && aligned(r, 16)) : K % e == 0);
-  const bool b_vec = aligned(B, 16) && ldb % e == 0 &&
-                     (b_contig ? (segs_ok && aligned(s, 16)) : K % e == 0);
-  const bool p_vec = plan->all_n_mult4 && aligned(partials, 16) && aligned(s, 16);
+  // members' probe vectors follow each other: r is n_members x M, s is n_members x N
+  const int64_t r_stride = batched ? plan->M : 0, s_stride = batched ? plan->N : 0;
+  const bool a_vec = aligned(A, 16) && lda % e == 0 && offsets_multiple_of(bl.a, bl.shape, e) &&
+                     (a_contig ? (segs_ok && aligned(r, 16) && r_stride % 4 == 0) : K % e == 0);
+  const bool b_vec = aligned(B, 16) && ldb % e == 0 && offsets_multiple_of(bl.b, bl.shape, e) &&
+                     (b_contig ? (segs_ok && aligned(s, 16) && s_stride % 4 == 0) : K % e == 0);
+  const bool p_vec = plan->all_n_mult4 && aligned(partials, 16) && aligned(s, 16) && s_stride % 4 == 0;
   cleave::VerifyPassArgs pass{};
-  pass.A = cleave::ProjectArgs{A, lda, v->d_row_segs, static_cast<int>(v->row_segs.size()), r, U, U_abs, K};
-  pass.B = cleave::ProjectArgs{B, ldb, v->d_col_segs, static_cast<int>(v->col_segs.size()), s, V, V_abs, K};
+  pass.A = cleave::ProjectArgs{A, lda, v->d_row_segs, static_cast<int>(v->row_segs.size()), r, U, U_abs, K,
+                               n_members, r_stride, bl.shape, bl.a};
+  pass.B = cleave::ProjectArgs{B, ldb, v->d_col_segs, static_cast<int>(v->col_segs.size()), s, V, V_abs, K,
+                               n_members, s_stride, bl.shape, bl.b};
   pass.bil = cleave::BilinearArgs{plan->d_tasks, v->d_items, static_cast<int64_t>(v->items.size()),
-                                  partials, r, s, v->d_item_sums};
+                                  partials, r, s, v->d_item_sums, batched ? 1 : 0, r_stride, s_stride};
   CLEAVE_HIP(cleave::launch_verify_pass(pass, dtype, a_contig, b_contig, a_vec && b_vec && p_vec, stream));
 
   cleave::VerdictArgs va{plan->d_tasks, static_cast<int64_t>(plan->tasks.size()),
                          v->d_task_row_seg, v->d_task_col_seg, v->d_task_first_item,
-                         v->d_item_sums, U, U_abs, V, V_abs, K, tol, lhs, rhs, scale, accept};
+                         v->d_item_sums, U, U_abs, V, V_abs, K, batched ? 1 : 0,
+                         static_cast<int>(v->row_segs.size()), static_cast<int>(v->col_segs.size()),
+                         tol, lhs, rhs, scale, accept};
   CLEAVE_HIP(cleave::launch_verdict(va, stream));
   return CLEAVE_OK;
+}
+
+}  // namespace
+
+extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int transA,
+                             const void* B, int64_t ldb, int transB, int dtype,
+                             const float* partials, const float* r, const float* s, double tol,
+                             double* lhs, double* rhs, double* scale, int32_t* accept,
+                             void* hip_stream) {
+  if (plan && plan->batch > 0) return CLEAVE_EINVAL;   // batched plans use the batched / grouped calls
+  return verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
+                     accept, BatchLayout{}, hip_stream);
+}
+
+extern "C" int cleave_verify_batched(cleave_plan* plan, const void* A, int64_t lda, int transA,
+                                     int64_t a_outer, int64_t a_inner, const void* B, int64_t ldb,
+                                     int transB, int64_t b_outer, int64_t b_inner, int64_t n_inner,
+                                     int dtype, const float* partials, const float* r, const float* s,
+                                     double tol, double* lhs, double* rhs, double* scale,
+                                     int32_t* accept, void* hip_stream) {
+  if (!plan || plan->batch < 1) return CLEAVE_EINVAL;
+  if (n_inner < 1 || n_inner > std::numeric_limits<uint32_t>::max() || plan->batch % n_inner != 0)
+    return CLEAVE_EINVAL;
+  if (a_outer < 0 || a_inner < 0 || b_outer < 0 || b_inner < 0) return CLEAVE_EINVAL;
+  return verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
+                     accept, strided_layout(n_inner, a_outer, a_inner, b_outer, b_inner, 0, 0), hip_stream);
+}
+
+extern "C" int cleave_verify_grouped(cleave_plan* plan, int64_t n_members, const void* const* A_list,
+                                     int64_t lda, int transA, const void* const* B_list, int64_t ldb,
+                                     int transB, int dtype, const float* partials, const float* r,
+                                     const float* s, double tol, double* lhs, double* rhs,
+                                     double* scale, int32_t* accept, void* hip_stream) {
+  if (!plan || plan->batch < 1 || plan->batch > cleave::kMaxGroup || n_members != plan->batch)
+    return CLEAVE_EINVAL;
+  if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  const int eb = dtype == CLEAVE_BF16 ? 2 : 4;
+  BatchLayout bl;
+  bl.shape.n_group = static_cast<uint32_t>(plan->batch);
+  const void* A = nullptr;
+  const void* B = nullptr;
+  int rc = group_offsets(A_list, plan->batch, eb, &bl.a, &A);
+  if (rc != CLEAVE_OK) return rc;
+  rc = group_offsets(B_list, plan->batch, eb, &bl.b, &B);
+  if (rc != CLEAVE_OK) return rc;
+  return verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
+                     accept, bl, hip_stream);
 }

@@ -138,6 +138,10 @@ hipError_t launch_reduce_adam_grouped(const ReduceArgs& args, const AdamArgs& h,
 //   out_abs[seg][k] = sum_{i in seg} |x(i, k)| * |w[seg.start + i]|
 // for k in [0, K).  reduce_contiguous = false: x(i, k) = src[i * ld + k] (the
 // summed index strides, k is contiguous); true: x(i, k) = src[k * ld + i].
+// Batched plans: the projection is made once per (member, segment); member g's
+// operand starts member_offset(at, batch, g) elements after src, its weights
+// g * w_stride entries after w, and its outputs follow member g-1's (index
+// (g * n_segs + seg) * K + k).  Plain plans: n_members = 1, offsets zero.
 struct ProjectArgs {
   const void* src;
   int64_t ld;               // elements
@@ -147,9 +151,15 @@ struct ProjectArgs {
   double* out;
   double* out_abs;
   int64_t K;
+  int n_members;
+  int64_t w_stride;
+  BatchShape batch;
+  MemberOffsets at;
 };
 
 // item_sums[item] = sum_{rows of the item} r[m0 + i] * sum_j P[i][j] * s[n0 + j].
+// Batched plans (batched != 0): task.gemm_id selects the member's probe vectors,
+// r_stride / s_stride entries apart.
 struct BilinearArgs {
   const cleave_task* tasks;
   const VerifyItem* items;
@@ -158,6 +168,8 @@ struct BilinearArgs {
   const float* r;
   const float* s;
   double* item_sums;
+  int batched;
+  int64_t r_stride, s_stride;
 };
 
 // The two projections and the bilinear items in one launch.  a_contig /
@@ -185,6 +197,8 @@ struct VerdictArgs {
   const double* V;
   const double* V_abs;
   int64_t K;
+  int batched;          // task.gemm_id selects the member's projections
+  int n_row_segs, n_col_segs;
   double tol;
   double* lhs;      // any of lhs, rhs, scale may be null
   double* rhs;

@@ -95,7 +95,10 @@ struct ProjectStrided {
   static constexpr int kSmemDoubles = 2 * (kThreads / 64) * KW;
 
   __device__ static void run(const ProjectArgs& a, int si, int64_t kblock, double* smem) {
-    const Segment seg = a.segs[si];
+    const int member = si / a.n_segs;
+    const Segment seg = a.segs[si - member * a.n_segs];
+    const int64_t moff = member_offset(a.at, a.batch, static_cast<uint32_t>(member));
+    const float* wv = a.w + member * a.w_stride;
     const int t = threadIdx.x;
     const int kc = t % KT;
     const int slice = t / KT;
@@ -107,9 +110,9 @@ struct ProjectStrided {
 #pragma unroll 4
       for (uint32_t i = slice; i < seg.len; i += SL) {
         const int64_t row = static_cast<int64_t>(seg.start) + i;
-        const double w = static_cast<double>(a.w[row]);
+        const double w = static_cast<double>(wv[row]);
         double x[VEC];
-        load_elems<EB, VEC>(a.src, row * a.ld + k, x);
+        load_elems<EB, VEC>(a.src, moff + row * a.ld + k, x);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           acc[e] = fma(x[e], w, acc[e]);
@@ -165,19 +168,22 @@ struct ProjectRows {
   static constexpr int kSmemDoubles = 0;
 
   __device__ static void run(const ProjectArgs& a, int si, int64_t kblock, double*) {
-    const Segment seg = a.segs[si];
+    const int member = si / a.n_segs;
+    const Segment seg = a.segs[si - member * a.n_segs];
+    const int64_t moff = member_offset(a.at, a.batch, static_cast<uint32_t>(member));
+    const float* wv = a.w + member * a.w_stride;
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
     for (int round = 0; round < ROUNDS; ++round) {
       const int64_t k = kblock * KW + ((threadIdx.x >> 6) * ROUNDS + round) * RPW + lane / LPR;
       // rows past K are read as row K-1 (no out-of-range access) and not stored
-      const int64_t base = (k < a.K ? k : a.K - 1) * a.ld + seg.start;
+      const int64_t base = moff + (k < a.K ? k : a.K - 1) * a.ld + seg.start;
       double acc = 0.0, acc_abs = 0.0;
 #pragma unroll 4
       for (uint32_t i = c * VEC; i < seg.len; i += LPR * VEC) {
         double x[VEC], w[VEC];
         load_elems<EB, VEC>(a.src, base + i, x);
-        load_weights<VEC>(a.w + seg.start + i, w);
+        load_weights<VEC>(wv + seg.start + i, w);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           acc = fma(x[e], w[e], acc);
@@ -206,8 +212,9 @@ __device__ __forceinline__ void bilinear_item(const BilinearArgs& a, int64_t it,
   const cleave_task task = a.tasks[item.task];
   const uint32_t n_len = task.n_len;
   const float* P = a.partials + task.partial_off + static_cast<uint64_t>(item.row0) * n_len;
-  const float* rr = a.r + task.m0 + item.row0;
-  const float* ss = a.s + task.n0;
+  const int64_t member = a.batched ? task.gemm_id : 0;
+  const float* rr = a.r + member * a.r_stride + task.m0 + item.row0;
+  const float* ss = a.s + member * a.s_stride + task.n0;
   const uint32_t count = item.rows * n_len;
   double acc = 0.0;
   if constexpr (VEC) {
@@ -288,8 +295,8 @@ __global__ __launch_bounds__(kThreads) void verify_pass_kernel(VerifyPassArgs a)
   __shared__ double smem[kSmem > 8 ? kSmem : 8];
   const int64_t kbA = (a.A.K + ProjA::KW - 1) / ProjA::KW;
   const int64_t kbB = (a.B.K + ProjB::KW - 1) / ProjB::KW;
-  const int64_t unitsA = kbA * a.A.n_segs;
-  const int64_t unitsB = kbB * a.B.n_segs;
+  const int64_t unitsA = kbA * a.A.n_segs * a.A.n_members;
+  const int64_t unitsB = kbB * a.B.n_segs * a.B.n_members;
   const int64_t proj = unitsA + unitsB;
   const int64_t total = proj + a.bil.n_items;
   // every `every`-th unit is a projection unit until they are used up, so that
@@ -319,8 +326,9 @@ __global__ __launch_bounds__(kThreads) void verdict_kernel(VerdictArgs a) {
   double lhs = 0.0;
   for (uint32_t i = a.task_first_item[t] + threadIdx.x; i < a.task_first_item[t + 1]; i += kThreads)
     lhs += a.item_sums[i];
-  const int64_t ro = static_cast<int64_t>(a.task_row_seg[t]) * a.K + task.k0;
-  const int64_t co = static_cast<int64_t>(a.task_col_seg[t]) * a.K + task.k0;
+  const int64_t member = a.batched ? task.gemm_id : 0;
+  const int64_t ro = (member * a.n_row_segs + a.task_row_seg[t]) * a.K + task.k0;
+  const int64_t co = (member * a.n_col_segs + a.task_col_seg[t]) * a.K + task.k0;
   double rhs = 0.0, scale = 0.0;
   for (uint32_t k = threadIdx.x; k < task.k_len; k += kThreads) {
     rhs = fma(a.U[ro + k], a.V[co + k], rhs);
@@ -377,7 +385,7 @@ hipError_t launch_verify_pass(const VerifyPassArgs& a, int dtype, bool a_contig,
   const int64_t kbA = (a.A.K + (a_contig ? kwRows : kwStrided / 2) - 1) / (a_contig ? kwRows : kwStrided / 2);
   const int64_t kbB = (a.B.K + (b_contig ? kwRows : kwStrided / 2) - 1) / (b_contig ? kwRows : kwStrided / 2);
   // (an upper bound for the strided fp32 vector case, exact otherwise up to a factor 2)
-  const int64_t units = kbA * a.A.n_segs + kbB * a.B.n_segs + a.bil.n_items;
+  const int64_t units = kbA * a.A.n_segs * a.A.n_members + kbB * a.B.n_segs * a.B.n_members + a.bil.n_items;
   if (units == 0) return hipSuccess;
   const dim3 grid(static_cast<unsigned>(units < (int64_t{1} << 20) ? units : (int64_t{1} << 20)));
   if (dtype == CLEAVE_BF16) {

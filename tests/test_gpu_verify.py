@@ -231,3 +231,125 @@ def test_verify_c4_heterogeneous_full_size_sampled():
         tasks, _ = planner.plan_explicit(g.M, g.N, g.K, band_h, col_w, ks, gemm_id=gid)
         _full_size_check(g, plan, tasks, cfg, cache, seed=7100 + gid)
         print("c4 verify", g.name, plan.num_tasks, "tasks", flush=True)
+
+
+# ---- batched and grouped plans (the attention products; the GEMMs of a DAG level) ----
+
+def oracle_batched(tasks, member_operands, parts, r, s, tol, per_member):
+    """Per task of a batched list: the oracle's check with the member's operands and
+    probe vectors.  member_operands(g) -> (opA, opB)."""
+    n = len(tasks)
+    lhs, rhs, scale, accept = np.zeros(n), np.zeros(n), np.zeros(n), np.zeros(n, dtype=np.int32)
+    cache = {}
+    for i, t in enumerate(tasks):
+        g = int(t["gemm_id"])
+        if g not in cache:
+            cache[g] = member_operands(g)
+        opA, opB = cache[g]
+        off, cnt = int(t["partial_off"]), int(t["m_len"]) * int(t["n_len"])
+        lhs[i], rhs[i], scale[i], ok = ov.verify_task(opA, opB, parts[off:off + cnt], t, r[g], s[g], tol)
+        accept[i] = int(ok)
+    return lhs, rhs, scale, accept
+
+
+@pytest.mark.parametrize("integer", [False, True])
+def test_verify_batched_attention_scores_matches_oracle(integer):
+    """Q K^T per sequence and head as one batched task list over token-major Q, K
+    (zero-copy strided views); blocks written by the library's own executor, one of
+    them corrupted afterwards."""
+    n_seq, H, s_len, d, tile = 2, 3, 192, 64, 128
+    G, ld = n_seq * H, H * d
+    Q = make_matrix(61, n_seq * s_len, ld, "bf16", integer_valued=integer)
+    Kt = make_matrix(62, n_seq * s_len, ld, "bf16", integer_valued=integer)
+    plan = cleave.plan_batched(s_len, s_len, d, tile, tile, 1, G)
+    tasks, elems = planner.plan_batched(s_len, s_len, d, tile, tile, 1, G)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    dQ, dK = Q.cuda(), Kt.cuda()
+    parts = torch.empty(elems, dtype=torch.float32, device="cuda")
+    strides = (s_len * ld, d)
+    cleave.execute_batched(plan, dQ, strides, dK, strides, H, parts, 0, 1)
+    bad = [2, len(tasks) - 3]
+    for i in bad:
+        parts[int(tasks[i]["partial_off"]) + 11] += 1000.0
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(63)
+    if integer:
+        r = (torch.randint(0, 2, (G, s_len), generator=gen, dtype=torch.int32).float() * 2 - 1)
+        s = (torch.randint(0, 2, (G, s_len), generator=gen, dtype=torch.int32).float() * 2 - 1)
+    else:
+        r = torch.randn((G, s_len), generator=gen)
+        s = torch.randn((G, s_len), generator=gen)
+    n = plan.num_tasks
+    out = {k: torch.full((n,), float("nan"), dtype=torch.float64, device="cuda") for k in ("lhs", "rhs", "scale")}
+    accept = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    cleave.verify_batched(plan, dQ, strides, dK, strides, H, parts, r.cuda(), s.cuda(), 1e-6, accept,
+                          out["lhs"], out["rhs"], out["scale"], transA=0, transB=1)
+    torch.cuda.synchronize()
+    Qd, Kd = og.widen(Q), og.widen(Kt)
+
+    def member(g):
+        a = np.ascontiguousarray(og.batch_view(Qd, g, H, s_len * ld, d, s_len, d))
+        b = np.ascontiguousarray(og.batch_view(Kd, g, H, s_len * ld, d, s_len, d))
+        return og.logical_operands(a, 0, b, 1)
+    ph = parts.cpu().numpy()
+    ref = oracle_batched(tasks, member, ph, r.numpy(), s.numpy(), 1e-6, True)
+    got = tuple(out[k].cpu().numpy() for k in ("lhs", "rhs", "scale")) + (accept.cpu().numpy(),)
+    if integer:
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b)
+    else:
+        sizes = np.zeros(n)
+        for i, t in enumerate(tasks):
+            g = int(t["gemm_id"])
+            m0, ml, n0, nl = (int(t[f]) for f in ("m0", "m_len", "n0", "n_len"))
+            off = int(t["partial_off"])
+            P = np.abs(ph[off:off + ml * nl].astype(np.float64)).reshape(ml, nl)
+            sizes[i] = np.abs(r[g].numpy()[m0:m0 + ml]) @ P @ np.abs(s[g].numpy()[n0:n0 + nl])
+        compare(tasks, got, ref, sizes)
+    assert set(np.flatnonzero(got[3] == 0)) == set(bad)
+
+
+@pytest.mark.parametrize("transA,transB", [(0, 0), (1, 0), (0, 1)])
+def test_verify_grouped_level_matches_oracle(transA, transB):
+    """Three same-shape GEMMs of a level (shared A, own B), K-split 2, one pointer per member."""
+    M, N, K, tile, S, n = 384, 264, 256, 128, 2, 3
+    A_log = make_matrix(71, M, K, "bf16")
+    B_logs = [make_matrix(72 + g, K, N, "bf16", std=0.02) for g in range(n)]
+    A = stored(A_log, transA)
+    Bs = [stored(b, transB) for b in B_logs]
+    plan = cleave.plan_batched(M, N, K, tile, tile, S, n)
+    tasks, elems = planner.plan_batched(M, N, K, tile, tile, S, n)
+    dA, dBs = A.cuda(), [b.cuda() for b in Bs]
+    parts = torch.empty(elems, dtype=torch.float32, device="cuda")
+    cleave.execute_grouped(plan, [dA] * n, dBs, parts, transA, transB)
+    bad = [1, len(tasks) // 2, len(tasks) - 1]
+    for i in bad:
+        parts[int(tasks[i]["partial_off"]) + 5] -= 500.0
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(75)
+    r, s = torch.randn((n, M), generator=gen), torch.randn((n, N), generator=gen)
+    cnt = plan.num_tasks
+    out = {k: torch.full((cnt,), float("nan"), dtype=torch.float64, device="cuda") for k in ("lhs", "rhs", "scale")}
+    accept = torch.full((cnt,), -1, dtype=torch.int32, device="cuda")
+    cleave.verify_grouped(plan, [dA] * n, dBs, parts, r.cuda(), s.cuda(), 1e-6, accept, out["lhs"], out["rhs"],
+                          out["scale"], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ph = parts.cpu().numpy()
+    ref = oracle_batched(tasks, lambda g: og.logical_operands(A, transA, Bs[g], transB), ph, r.numpy(), s.numpy(),
+                         1e-6, True)
+    got = tuple(out[k].cpu().numpy() for k in ("lhs", "rhs", "scale")) + (accept.cpu().numpy(),)
+    sizes = np.zeros(cnt)
+    for i, t in enumerate(tasks):
+        g = int(t["gemm_id"])
+        m0, ml, n0, nl = (int(t[f]) for f in ("m0", "m_len", "n0", "n_len"))
+        off = int(t["partial_off"])
+        P = np.abs(ph[off:off + ml * nl].astype(np.float64)).reshape(ml, nl)
+        sizes[i] = np.abs(r[g].numpy()[m0:m0 + ml]) @ P @ np.abs(s[g].numpy()[n0:n0 + nl])
+    compare(tasks, got, ref, sizes)
+    assert set(np.flatnonzero(got[3] == 0)) == set(bad)
+    # plain plans are refused by the batched forms and batched plans by the plain one
+    plain = cleave.plan_uniform(M, N, K, tile, tile, S)
+    with pytest.raises(cleave.CleaveError):
+        cleave.verify_grouped(plain, [dA], dBs[:1], parts, r.cuda(), s.cuda(), 1e-6, accept)
+    with pytest.raises(cleave.CleaveError):
+        cleave.verify(plan, dA, dBs[0], parts, r.cuda(), s.cuda(), 1e-6, accept, transA=transA, transB=transB)
