@@ -503,6 +503,11 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
     args.C = asm_to.C;
     args.ldc = asm_to.ldc;
     args.c_bf16 = asm_to.out_dtype == CLEAVE_BF16 ? 1 : 0;
+    // block origins and row lengths are multiples of 8 elements whenever `vec` holds
+    args.out_vec = !vec ? 0
+                   : !asm_to.C ? aligned(partials, 16)
+                               : (asm_to.ldc % 4 == 0 && aligned(asm_to.C, args.c_bf16 ? 8 : 16) &&
+                                  offsets_multiple_of(bl.c, bl.shape, 4));
     // bf16 with 16-byte loads: items made of whole K steps go to the direct
     // kernel, the others (if any) to the staged one.  Which kernel computes a
     // block depends only on the block's own task record.

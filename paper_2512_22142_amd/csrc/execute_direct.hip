@@ -27,6 +27,12 @@
 //     k row i/4 and receives column i of the 4 x 16 block), two reads per
 //     fragment; the XOR spreads the four k rows of a read over the banks.
 //
+// Stores: a full sub-tile leaves through a 4 KB row-major image per wave in
+// LDS behind the ring, so that every store instruction writes whole 128-byte
+// lines (a quarter of the store instructions of the accumulator layout, none
+// of them held up by the limit of 63 outstanding operations); outputs that
+// are only element-aligned and clipped sub-tiles take 4-byte stores.
+//
 // Order of accumulation per output element: ascending K steps, inside a step
 // ascending 16-element sub-steps, one MFMA each -- a function of the task
 // record only (and the same for every shape), hence bitwise reproducible on
@@ -270,10 +276,13 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   // one-step items free no stage early) the ring is filled from empty after the
   // item's last step, ahead of its stores.
   static_assert(STAGES == 2, "the hand-over between items is written for a ring of two stages");
-  constexpr int kTileStores = full_tile_stores<MB, NB>();   // store instructions per lane and full sub-tile
+  // Store instructions per lane: a full sub-tile whose target takes 16-byte
+  // stores goes through the wave's block image in LDS (behind the ring).
+  constexpr int kTileStores = MB * staged_stores_per_block_row<NB>();
   constexpr int kHalfStores = kTileStores / 2;
-  constexpr int kBehindCheck = kHalfStores < 63 ? kHalfStores : 63;
-  static_assert(MB % 2 == 0, "the epilogue stores a sub-tile in two halves of block rows");
+  constexpr int kBehindCheck = kHalfStores;
+  static_assert(MB % 2 == 0 && kTileStores <= 63, "the epilogue stores a sub-tile in two halves of block rows");
+  unsigned char* const image = smem + STAGES * kStage + wave * kBlockImageBytes;
 
   const int64_t stride = gridDim.x;
   if (static_cast<int64_t>(blockIdx.x) >= args.n_items) return;
@@ -289,10 +298,9 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   WorkItem after_next;
   // How the current item's first two steps got into the ring.
   //   kFilled:             ring filled from empty, nothing issued since.
-  //   kFilledBehindStores: ring filled from empty, then the previous item's
-  //     stores: more of them than the vector-memory counter can hold (63), and
-  //     the counter retires in issue order, so the loads have landed once at
-  //     most 63 operations are outstanding.
+  //   kFilledBehindStores: ring filled from empty, then exactly kTileStores
+  //     stores of the previous item: the counter retires in issue order, so the
+  //     loads have landed once at most that many operations are outstanding.
   //   kPrefetched:         fetched during the previous item's last two steps;
   //     step 0 was waited for at that item's last barrier (its first fragments
   //     are already in registers), step 1 between the two halves of its stores.
@@ -336,14 +344,19 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       }
     }
   };
-  auto mma = [&](int buf) {
+  // `fresh`: the first product of a work item starts from zero (a constant
+  // operand of the instruction: no pass over the accumulators to clear them).
+  auto mma = [&](int buf, auto fresh_tag) {
+    constexpr bool FRESH = decltype(fresh_tag)::value;
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < NB; ++j)
+      for (int j = 0; j < NB; ++j) {
+        f32x16 sum = acc[i][j];
+        if constexpr (FRESH) sum = f32x16{};
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]),
-            acc[i][j], 0, 0, 0);
+            __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]), sum, 0, 0, 0);
+      }
   };
 
   // Instruction order of one sub-step, as a hint to the scheduler: the MFMAs
@@ -366,21 +379,15 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     const int steps = c.steps;
     const bool has_next = it_next < args.n_items;
     const bool interior = c.m_valid == TM && c.n_valid == TN;
+    const bool wide = interior && args.out_vec;   // stores of whole lines through the block image
     // hand the ring over without draining it
-    const bool cont = has_next && interior && nx.m_valid == TM && nx.n_valid == TN && steps >= 2;
-
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    const bool cont = has_next && wide && nx.m_valid == TM && nx.n_valid == TN && steps >= 2;
 
     // Step 0 must have landed.  All earlier fragment reads of this workgroup
     // completed before the previous item's final barrier.
     if (entry != kPrefetched) {
       if (entry == kFilledBehindStores) {
-        CLEAVE_WAIT_BARRIER(63);
+        CLEAVE_WAIT_BARRIER(kTileStores);
       } else if (steps >= STAGES) {
         CLEAVE_WAIT_BARRIER(LPS);
       } else {
@@ -399,15 +406,16 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     // while the last sub-step multiplies.  MID: a step with at least two more
     // steps of this item behind it and not the item's first -- no case
     // distinctions, the loop body of long chunks.
-    auto k_step = [&](auto mid_tag, int s) {
+    auto k_step = [&](auto mid_tag, auto first_tag, int s) {
       constexpr bool MID = decltype(mid_tag)::value;
+      constexpr bool FIRST = decltype(first_tag)::value;   // the item's step 0
       const int st = (s + phase) & 1;
       const uint32_t cur = st ? kStage : 0;
       const uint32_t oth = st ? 0 : kStage;
       auto sub = [&](auto j_tag) {
         constexpr int J = decltype(j_tag)::value;
         read_frags(cur, int_c<J + 1>{}, (J + 1) & 1);
-        mma(J & 1);
+        mma(J & 1, std::bool_constant<FIRST && J == 0>{});
         interleave();
       };
       sub(int_c<0>{});
@@ -426,7 +434,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
           // wait for the previous item's stores either
           CLEAVE_WAIT_BARRIER(63);
         } else if (s == 0 && entry == kFilledBehindStores) {
-          CLEAVE_WAIT_BARRIER(63);
+          CLEAVE_WAIT_BARRIER(kTileStores);
         } else if (s == 0 && entry == kPrefetched) {
           // step 1 was waited for before the second half of the previous item's stores
           CLEAVE_WAIT_BARRIER(kBehindCheck);
@@ -441,13 +449,13 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         if (s == 0) after_next = load_item(it_next + stride < args.n_items ? it_next + stride : last_item);
         if (!last || cont) read_frags(oth, int_c<0>{}, 0);
       }
-      mma((kSub - 1) & 1);
+      mma((kSub - 1) & 1, std::false_type{});
       interleave();
     };
-    k_step(std::false_type{}, 0);
+    k_step(std::false_type{}, std::true_type{}, 0);
     int s = 1;
-    for (; s + STAGES < steps; ++s) k_step(std::true_type{}, s);
-    for (; s < steps; ++s) k_step(std::false_type{}, s);
+    for (; s + STAGES < steps; ++s) k_step(std::true_type{}, std::false_type{}, s);
+    for (; s < steps; ++s) k_step(std::false_type{}, std::false_type{}, s);
 
     // Every wave is past the last step's barrier, hence past all of its
     // fragment reads of this item.
@@ -461,18 +469,23 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       // between the two halves of the stores: the first half keeps the memory
       // pipeline busy meanwhile, and the second half then trails the check, so
       // that the next item's first barrier finds at most kBehindCheck
-      // operations outstanding without any store having to complete.
-      store_tile_rows<MB, NB, 0, MB / 2>(acc, target, bf16_out, row0, col0);
+      // operations outstanding without any store having to complete.  The
+      // block image is this wave's own: no barrier between the halves.
+      store_tile_rows_staged<MB, NB, 0, MB / 2>(acc, target, bf16_out, image, wm * S::WTM, wn * S::WTN, lane);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kBehindCheck) : "memory");
-      store_tile_rows<MB, NB, MB / 2, MB>(acc, target, bf16_out, row0, col0);
+      store_tile_rows_staged<MB, NB, MB / 2, MB>(acc, target, bf16_out, image, wm * S::WTM, wn * S::WTN, lane);
       entry = kPrefetched;
       phase = (phase + steps) & 1;
     } else {
       // The ring is free: the next item's ring fill is issued before this
       // item's stores so that its latency hides behind them.
       if (has_next) fill_ring(nx);
-      store_tile<MB, NB>(acc, target, bf16_out, row0, col0, m_valid, n_valid, interior);
-      entry = (interior && kTileStores >= 63) ? kFilledBehindStores : kFilled;
+      if (wide) {
+        store_tile_rows_staged<MB, NB, 0, MB>(acc, target, bf16_out, image, wm * S::WTM, wn * S::WTN, lane);
+      } else {
+        store_tile<MB, NB>(acc, target, bf16_out, row0, col0, m_valid, n_valid, interior);
+      }
+      entry = wide ? kFilledBehindStores : kFilled;
       phase = 0;
     }
     if (!has_next) break;
@@ -484,7 +497,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 
 template <typename S, bool A_K, bool B_K>
 hipError_t launch_one(const ExecuteArgs& args, int grid, hipStream_t stream) {
-  constexpr size_t lds = S::STAGES * S::kStage;
+  constexpr size_t lds = S::STAGES * S::kStage + S::NW * kBlockImageBytes;
   hipLaunchKernelGGL((execute_direct_kernel<S, A_K, B_K>), dim3(grid), dim3(S::NT), lds, stream, args);
   return hipGetLastError();
 }
@@ -493,7 +506,7 @@ template <typename S, bool A_K, bool B_K>
 hipError_t configure_one() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(execute_direct_kernel<S, A_K, B_K>),
                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                             static_cast<int>(S::STAGES * S::kStage));
+                             static_cast<int>(S::STAGES * S::kStage + S::NW * kBlockImageBytes));
 }
 
 template <typename S>

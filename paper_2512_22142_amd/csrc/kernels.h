@@ -50,6 +50,9 @@ struct ExecuteArgs {
   void* C;
   int64_t ldc;
   int c_bf16;
+  // The output (partials, or C in assemble mode) takes a 16-byte (fp32) or
+  // 8-byte (bf16) store at every fourth column of every sub-tile row.
+  int out_vec;
 };
 
 // Enqueues the execute kernel for one tile class.  `vec` selects the 16-byte

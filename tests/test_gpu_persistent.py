@@ -64,3 +64,49 @@ def test_many_short_items_per_workgroup_exact(cls, steps, transA, transB):
             assert np.array_equal(block_of(parts, t), ref[m0:m0 + ml, n0:n0 + nl]), (int(t["tile_id"]), s)
         total += ref
     assert np.array_equal(C, total)
+
+
+@pytest.mark.parametrize("out", ["partials", "assembled_f32", "assembled_bf16"])
+def test_outputs_that_only_take_element_stores_exact(out):
+    """The fast kernel writes full sub-tiles with 16-byte stores when the output
+    allows them.  Here it does not: the partial workspace starts one element
+    into its allocation, the assembled output has an odd row pitch and starts
+    one element in.  Same kernel, element stores, several items per workgroup,
+    every value equal to the oracle's."""
+    M, N, tile = 8192, 4096, 256
+    S = 4 if out == "partials" else 1
+    K = 2 * K_STEP * S
+    assert (M // tile) * (N // tile) * S >= 2 * _resident_workgroups(1)
+    a = make_matrix(701, M, K, "bf16", integer_valued=True)
+    b = make_matrix(702, K, N, "bf16", integer_valued=True)
+    plan = cleave.plan_uniform(M, N, K, tile, tile, S)
+    tasks, elems = planner.plan_uniform(M, N, K, tile, tile, S)
+    dA, dB = a.cuda(), b.cuda()
+    opA, opB = og.logical_operands(a, 0, b, 0)
+    ref = og.gemm(opA, opB)
+    if out == "partials":
+        raw = torch.full((elems + 1,), float("nan"), dtype=torch.float32, device="cuda")
+        parts = raw[1:]
+        assert parts.data_ptr() % 16 == 4
+        cleave.execute(plan, dA, dB, parts)
+        assert "direct" in plan.last_kernel
+        torch.cuda.synchronize()
+        host = parts.cpu().numpy()
+        for s in range(S):
+            ref_s = og.gemm(opA, opB, s * K // S, (s + 1) * K // S)
+            for t in tasks[tasks["ksplit_idx"] == s]:
+                m0, ml, n0, nl = int(t["m0"]), int(t["m_len"]), int(t["n0"]), int(t["n_len"])
+                assert np.array_equal(block_of(host, t), ref_s[m0:m0 + ml, n0:n0 + nl]), (int(t["tile_id"]), s)
+        assert np.isnan(raw[:1].cpu().numpy()).all()
+    else:
+        dt = torch.float32 if out == "assembled_f32" else torch.bfloat16
+        wide = torch.full((M, N + 3), float("nan"), dtype=dt, device="cuda")
+        C = wide[:, 1:N + 1]
+        cleave.execute_assemble(plan, dA, dB, C)
+        assert "direct" in plan.last_kernel
+        torch.cuda.synchronize()
+        got = C.float().cpu().numpy()
+        want = ref if dt == torch.float32 else torch.from_numpy(ref).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(got, want)
+        pad = torch.cat([wide[:, :1], wide[:, N + 1:]], dim=1).float().cpu().numpy()
+        assert np.isnan(pad).all()          # nothing written outside the view
