@@ -35,9 +35,9 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "4ec236cdf7456416383dc4106118f8a8bc1d4ab17c5ef43a954d80c3c0d434ae",
-    "execute_bytes_per_launch": (2.0 * 225531 + 388535) * 1024,
-    "reduce_bytes_per_launch": (2.0 * 194739 + 97134) * 1024,
+    "sources_sha256": "262c43bd6cd45ec8b9923951a70caa37337d7cbe5a4f2777b080591c082bfa3b",
+    "execute_bytes_per_launch": (2.0 * 225733 + 388535) * 1024,
+    "reduce_bytes_per_launch": (2.0 * 194743 + 97134) * 1024,
 }
 
 
@@ -200,6 +200,68 @@ def measure_layer(cleave, torch, config_name, steps, warmup, group_levels=False)
     return dict(locals())
 
 
+def device_state_under_load(torch, step, seconds=0.6, period=0.01):
+    """Median board power and reported shader clock while `step` runs back to
+    back; None where the driver does not expose the file."""
+    import glob
+    import statistics
+    import threading
+    import time
+
+    def first(pattern):
+        found = sorted(glob.glob(pattern))
+        return found[0] if found else None
+
+    power_file = first("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or first(
+        "/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+    cap_file = first("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+    sclk_file = first("/sys/class/drm/card*/device/pp_dpm_sclk")
+    power, sclk = [], []
+    stop = threading.Event()
+
+    def sample():
+        while not stop.is_set():
+            try:
+                if power_file:
+                    power.append(int(open(power_file).read()) / 1e6)
+                if sclk_file:
+                    cur = [l for l in open(sclk_file).read().splitlines() if l.rstrip().endswith("*")]
+                    if cur:
+                        sclk.append(float(cur[0].split(":")[1].lower().replace("mhz", "").replace("*", "")))
+            except (OSError, ValueError, IndexError):
+                pass
+            time.sleep(period)
+
+    for _ in range(3):                   # the clock governor reacts within tens of milliseconds
+        step()
+    torch.cuda.synchronize()
+    t = threading.Thread(target=sample)
+    t0 = time.time()
+    t.start()
+    while time.time() - t0 < seconds:
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+    stop.set()
+    t.join()
+    # the first samples still see the ramp: keep the later two thirds
+    power, sclk = power[len(power) // 3:], sclk[len(sclk) // 3:]
+    cap = None
+    try:
+        cap = int(open(cap_file).read()) / 1e6 if cap_file else None
+    except (OSError, ValueError):
+        pass
+    return {
+        "board_power_w_median": round(statistics.median(power), 1) if power else None,
+        "board_power_cap_w": cap,
+        "reported_sclk_mhz_median": round(statistics.median(sclk), 1) if sclk else None,
+        "nominal_sclk_mhz": 2400,
+        "samples": len(power),
+        "source": "sysfs hwmon power1_input / pp_dpm_sclk, sampled every %d ms while the step repeats" % int(period * 1e3),
+        "note": "roofline.peak assumes the nominal clock",
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -217,6 +279,8 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
     ap.add_argument("--other-steps", type=int, default=5)
+    ap.add_argument("--no-device-state", action="store_true",
+                    help="skip the sampling of board power and reported clock while the step runs")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy, 10 times (reference "
@@ -332,6 +396,12 @@ def main():
                                "note": "the %d launches of a step captured once and replayed; `value` is the "
                                        "eager figure" % (2 * len(launches))}
         del graph
+
+    # ---- board power and reported clock while the step runs (information) -----
+    # Sampled from the driver's sysfs files in a thread of this process, over
+    # untimed repetitions of the step behind the timed region.
+    if not args.no_device_state:
+        result["device_state"] = device_state_under_load(torch, step)
 
     # ---- returned-block check (outside the timed step; reported on its own) -
     if not args.no_verify:
