@@ -280,8 +280,10 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   // stores goes through the wave's block image in LDS (behind the ring).
   constexpr int kTileStores = MB * staged_stores_per_block_row<NB>();
   constexpr int kHalfStores = kTileStores / 2;
-  constexpr int kBehindCheck = kHalfStores;
-  static_assert(MB % 2 == 0 && kTileStores <= 63, "the epilogue stores a sub-tile in two halves of block rows");
+  // "at most n operations outstanding" for n stores issued last: the counter holds 63 at most
+  constexpr int kBehindCheck = kHalfStores < 63 ? kHalfStores : 63;
+  constexpr int kBehindTile = kTileStores < 63 ? kTileStores : 63;
+  static_assert(MB % 2 == 0, "the epilogue stores a sub-tile in two halves of block rows");
   unsigned char* const image = smem + STAGES * kStage + wave * kBlockImageBytes;
 
   const int64_t stride = gridDim.x;
@@ -300,7 +302,8 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   //   kFilled:             ring filled from empty, nothing issued since.
   //   kFilledBehindStores: ring filled from empty, then exactly kTileStores
   //     stores of the previous item: the counter retires in issue order, so the
-  //     loads have landed once at most that many operations are outstanding.
+  //     loads have landed once at most that many operations are outstanding
+  //     (or 63, all the counter can hold, if the stores are more than that).
   //   kPrefetched:         fetched during the previous item's last two steps;
   //     step 0 was waited for at that item's last barrier (its first fragments
   //     are already in registers), step 1 between the two halves of its stores.
@@ -387,7 +390,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
     // completed before the previous item's final barrier.
     if (entry != kPrefetched) {
       if (entry == kFilledBehindStores) {
-        CLEAVE_WAIT_BARRIER(kTileStores);
+        CLEAVE_WAIT_BARRIER(kBehindTile);
       } else if (steps >= STAGES) {
         CLEAVE_WAIT_BARRIER(LPS);
       } else {
@@ -434,7 +437,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
           // wait for the previous item's stores either
           CLEAVE_WAIT_BARRIER(63);
         } else if (s == 0 && entry == kFilledBehindStores) {
-          CLEAVE_WAIT_BARRIER(kTileStores);
+          CLEAVE_WAIT_BARRIER(kBehindTile);
         } else if (s == 0 && entry == kPrefetched) {
           // step 1 was waited for before the second half of the previous item's stores
           CLEAVE_WAIT_BARRIER(kBehindCheck);
