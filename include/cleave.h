@@ -332,6 +332,26 @@ int cleave_verify(cleave_plan* plan,
                   double* lhs, double* rhs, double* scale, int32_t* accept,
                   void* hip_stream);
 
+/* cleave_verify and cleave_reduce in one pass over the partial blocks (Sec. 6
+ * and Sec. 3.2: the parameter server checks the blocks the devices return and
+ * aggregates them): every partial element is read once, for its check and for
+ * the sum.  lhs, rhs, scale, accept: as cleave_verify defines them (rhs and
+ * scale the same bits as cleave_verify's; lhs summed over shorter runs of rows,
+ * hence equal up to fp64 rounding, exactly equal for small integers).  C, ldc,
+ * out_dtype: as for cleave_reduce; C
+ * is bit for bit what cleave_reduce writes -- the sum of all S blocks of a tile
+ * whatever the verdicts, so a caller that finds a block rejected re-issues the
+ * task and aggregates again.  Tiles with more than 8 splits make the call run
+ * the two passes one after the other (same results).  Plain plans only.
+ * Scratch and the no-overlap rule as for cleave_verify.
+ * CLEAVE_EINVAL: as for cleave_verify and cleave_reduce. */
+int cleave_verify_reduce(cleave_plan* plan,
+                         const void* A, int64_t lda, int transA,
+                         const void* B, int64_t ldb, int transB, int dtype,
+                         const float* partials, const float* r, const float* s, double tol,
+                         double* lhs, double* rhs, double* scale, int32_t* accept,
+                         void* C, int64_t ldc, int out_dtype, void* hip_stream);
+
 /* The same check for a plan made by cleave_plan_batched (the attention
  * products of Sec. 3.1's table, or the same-shape GEMMs of a DAG level): every
  * task of every member is checked against that member's operands.  Members are

@@ -45,6 +45,7 @@ _BINDING_NAMES = (
     "reduce_residual",
     "verify",
     "verify_batched",
+    "verify_reduce",
     "verify_grouped",
     "version",
 )

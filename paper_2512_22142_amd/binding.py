@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped", "cleave_verify_batched", "cleave_verify_grouped",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped", "cleave_verify_batched", "cleave_verify_grouped", "cleave_verify_reduce",
 )
 
 
@@ -126,6 +126,9 @@ def _load():
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
+    lib.cleave_verify_reduce.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
+                                         p, p, p, ctypes.c_double, p, p, p, p, p, i64, ctypes.c_int, p]
+    lib.cleave_verify_reduce.restype = ctypes.c_int
     lib.cleave_verify_batched.argtypes = [p, p, i64, ctypes.c_int, i64, i64, p, i64, ctypes.c_int, i64, i64, i64,
                                           ctypes.c_int, p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify_batched.restype = ctypes.c_int
@@ -489,6 +492,23 @@ def _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale):
             vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
             vec(scale, torch.float64, plan.num_tasks, "scale", True),
             vec(accept, torch.int32, plan.num_tasks, "accept"))
+
+
+def verify_reduce(plan, A, B, partials, r, s, tol, accept, C, lhs=None, rhs=None, scale=None,
+                  transA=0, transB=0, stream=None):
+    """cleave_verify_reduce: the check of cleave_verify and the aggregation of
+    cleave_reduce in one pass over the partial blocks (plain plans)."""
+    a_ptr, lda = _matrix(A, "A")
+    b_ptr, ldb = _matrix(B, "B")
+    c_ptr, ldc = _matrix(C, "C")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same dtype")
+    if tuple(C.shape) != (plan.M, plan.N):
+        raise ValueError("C must be %d x %d" % (plan.M, plan.N))
+    pp, rp, sp, lp, hp, cp, ap = _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale)
+    _check(_lib.cleave_verify_reduce(plan._h, a_ptr, lda, int(transA), b_ptr, ldb, int(transB), _dtype_code(A),
+                                     pp, rp, sp, float(tol), lp, hp, cp, ap, c_ptr, ldc, _dtype_code(C),
+                                     _stream_ptr(stream)), "cleave_verify_reduce")
 
 
 def verify_batched(plan, A, a_strides, B, b_strides, n_inner, partials, r, s, tol, accept, lhs=None, rhs=None,

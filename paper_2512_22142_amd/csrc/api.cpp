@@ -34,13 +34,14 @@ bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p
 void free_verify_device(cleave::VerifyTables* v) {
   if (!v) return;
   void* ptrs[] = {v->d_row_segs, v->d_col_segs, v->d_task_row_seg, v->d_task_col_seg,
-                  v->d_items, v->d_task_first_item, v->d_proj, v->d_item_sums};
+                  v->d_items, v->d_task_first_item, v->d_agg_items, v->d_agg_first_item,
+                  v->d_agg_item_sums, v->d_proj, v->d_item_sums};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   v->d_row_segs = v->d_col_segs = nullptr;
-  v->d_task_row_seg = v->d_task_col_seg = v->d_task_first_item = nullptr;
-  v->d_items = nullptr;
-  v->d_proj = v->d_item_sums = nullptr;
+  v->d_task_row_seg = v->d_task_col_seg = v->d_task_first_item = v->d_agg_first_item = nullptr;
+  v->d_items = v->d_agg_items = nullptr;
+  v->d_proj = v->d_item_sums = v->d_agg_item_sums = nullptr;
 }
 
 void free_subset_ring(cleave::SubsetRing* r) {
@@ -796,11 +797,15 @@ extern "C" int cleave_reduce_grouped(cleave_plan* plan, const float* partials, i
   return reduce_impl(plan, partials, const_cast<void*>(C), ldc, out_dtype, bl, hip_stream);
 }
 
+#ifndef CLEAVE_AGG_ELEMS
+#define CLEAVE_AGG_ELEMS 8192
+#endif
+
 namespace {
 
 // Host tables of the returned-block check (built once per plan) and their
 // device copies plus scratch (once per device the plan is used on).
-int ensure_verify_tables(cleave_plan* p) {
+int ensure_verify_tables_host(cleave_plan* p) {
   using cleave::Segment;
   using cleave::VerifyItem;
   if (!p->verify) {
@@ -824,6 +829,7 @@ int ensure_verify_tables(cleave_plan* p) {
         const uint32_t index = static_cast<uint32_t>(&t - p->tasks.data());
         for (uint32_t r0 = 0; r0 < t.m_len; r0 += rows_per)
           v->items.push_back(VerifyItem{index, r0, std::min(rows_per, t.m_len - r0), 0});
+        v->max_ksplit = std::max(v->max_ksplit, t.ksplit_cnt);
         if (v->items.size() > std::numeric_limits<uint32_t>::max()) {
           delete v;
           return CLEAVE_EINVAL;
@@ -841,9 +847,15 @@ int ensure_verify_tables(cleave_plan* p) {
     }
     p->verify = v;
   }
+  return CLEAVE_OK;
+}
+
+int ensure_verify_tables(cleave_plan* p) {
+  int rc = ensure_verify_tables_host(p);
+  if (rc != CLEAVE_OK) return rc;
   cleave::VerifyTables* v = p->verify;
   if (v->d_items || p->tasks.empty()) return CLEAVE_OK;
-  int rc = upload_vector(v->row_segs, &v->d_row_segs);
+  rc = upload_vector(v->row_segs, &v->d_row_segs);
   if (rc == CLEAVE_OK) rc = upload_vector(v->col_segs, &v->d_col_segs);
   if (rc == CLEAVE_OK) rc = upload_vector(v->task_row_seg, &v->d_task_row_seg);
   if (rc == CLEAVE_OK) rc = upload_vector(v->task_col_seg, &v->d_task_col_seg);
@@ -862,14 +874,73 @@ int ensure_verify_tables(cleave_plan* p) {
   return rc;
 }
 
+// Tables of the fused check + aggregation (first fused call on the plan, after
+// ensure_verify_tables): runs of rows of ~kAggElemsPerItem output elements.
+int ensure_aggregate_tables(cleave_plan* p) {
+  using cleave::VerifyItem;
+  cleave::VerifyTables* v = p->verify;
+  if (v->d_agg_items || p->tasks.empty()) return CLEAVE_OK;
+  if (v->agg_first_item.empty()) {
+    try {
+      constexpr uint32_t kAggElemsPerItem = CLEAVE_AGG_ELEMS;
+      uint64_t slots = 0;
+      v->agg_first_item.push_back(0);
+      for (const cleave_task& t : p->tasks) {
+        const uint32_t rows_per = std::max<uint32_t>(1, kAggElemsPerItem / t.n_len);
+        const uint32_t index = static_cast<uint32_t>(&t - p->tasks.data());
+        for (uint32_t r0 = 0, j = 0; r0 < t.m_len; r0 += rows_per, ++j) {
+          if (t.ksplit_idx == 0)
+            v->agg_items.push_back(VerifyItem{index, r0, std::min(rows_per, t.m_len - r0),
+                                              static_cast<uint32_t>(slots) + j});
+        }
+        slots += (t.m_len + rows_per - 1) / rows_per;
+        if (slots > std::numeric_limits<uint32_t>::max()) {
+          v->agg_items.clear();
+          v->agg_first_item.clear();
+          return CLEAVE_EINVAL;
+        }
+        v->agg_first_item.push_back(static_cast<uint32_t>(slots));
+      }
+    } catch (const std::bad_alloc&) {
+      v->agg_items.clear();
+      v->agg_first_item.clear();
+      return CLEAVE_ENOMEM;
+    }
+  }
+  int rc = upload_vector(v->agg_items, &v->d_agg_items);
+  if (rc == CLEAVE_OK) rc = upload_vector(v->agg_first_item, &v->d_agg_first_item);
+  if (rc == CLEAVE_OK) {
+    const hipError_t e = hipMalloc(reinterpret_cast<void**>(&v->d_agg_item_sums),
+                                   static_cast<size_t>(v->agg_first_item.back()) * sizeof(double));
+    if (e == hipErrorOutOfMemory) rc = CLEAVE_ENOMEM;
+    else if (e != hipSuccess) rc = hip_fail(e);
+  }
+  if (rc != CLEAVE_OK) {
+    for (void* q : {static_cast<void*>(v->d_agg_items), static_cast<void*>(v->d_agg_first_item),
+                    static_cast<void*>(v->d_agg_item_sums)})
+      if (q) (void)hipFree(q);
+    v->d_agg_items = nullptr;
+    v->d_agg_first_item = nullptr;
+    v->d_agg_item_sums = nullptr;
+  }
+  return rc;
+}
+
 }  // namespace
 
 namespace {
 
+// Where the fused pass writes the aggregated output (C == nullptr: check only).
+struct AggregateTarget {
+  void* C = nullptr;
+  int64_t ldc = 0;
+  int out_dtype = CLEAVE_F32;
+};
+
 int verify_impl(cleave_plan* plan, const void* A, int64_t lda, int transA, const void* B, int64_t ldb,
                 int transB, int dtype, const float* partials, const float* r, const float* s, double tol,
                 double* lhs, double* rhs, double* scale, int32_t* accept, const BatchLayout& bl,
-                void* hip_stream) {
+                void* hip_stream, const AggregateTarget& agg = AggregateTarget{}) {
   if (!plan || !A || !B || !partials || !r || !s || !accept) return CLEAVE_EINVAL;
   if (dtype != CLEAVE_F32 && dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
   if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return CLEAVE_EINVAL;
@@ -921,11 +992,31 @@ int verify_impl(cleave_plan* plan, const void* A, int64_t lda, int transA, const
                                n_members, s_stride, bl.shape, bl.b};
   pass.bil = cleave::BilinearArgs{plan->d_tasks, v->d_items, static_cast<int64_t>(v->items.size()),
                                   partials, r, s, v->d_item_sums, batched ? 1 : 0, r_stride, s_stride};
-  CLEAVE_HIP(cleave::launch_verify_pass(pass, dtype, a_contig, b_contig, a_vec && b_vec && p_vec, stream));
+  const uint32_t* first_item = v->d_task_first_item;
+  const double* item_sums = v->d_item_sums;
+  if (agg.C) {
+    rc = ensure_aggregate_tables(plan);
+    if (rc != CLEAVE_OK) return rc;
+    first_item = v->d_agg_first_item;
+    item_sums = v->d_agg_item_sums;
+    const int ob = agg.out_dtype == CLEAVE_BF16 ? 2 : 4;
+    const bool c_vec = agg.ldc % 4 == 0 && aligned(agg.C, 4 * ob);
+    cleave::VerifyReducePassArgs fused{};
+    fused.A = pass.A;
+    fused.B = pass.B;
+    fused.bil = pass.bil;
+    fused.bil.item_sums = v->d_agg_item_sums;
+    fused.agg = cleave::AggregateArgs{v->d_agg_items, static_cast<int64_t>(v->agg_items.size()),
+                                      v->d_agg_first_item, agg.C, agg.ldc, agg.out_dtype == CLEAVE_BF16 ? 1 : 0};
+    CLEAVE_HIP(cleave::launch_verify_reduce_pass(fused, dtype, a_contig, b_contig,
+                                                 a_vec && b_vec && p_vec && c_vec, stream));
+  } else {
+    CLEAVE_HIP(cleave::launch_verify_pass(pass, dtype, a_contig, b_contig, a_vec && b_vec && p_vec, stream));
+  }
 
   cleave::VerdictArgs va{plan->d_tasks, static_cast<int64_t>(plan->tasks.size()),
-                         v->d_task_row_seg, v->d_task_col_seg, v->d_task_first_item,
-                         v->d_item_sums, U, U_abs, V, V_abs, K, batched ? 1 : 0,
+                         v->d_task_row_seg, v->d_task_col_seg, first_item,
+                         item_sums, U, U_abs, V, V_abs, K, batched ? 1 : 0,
                          static_cast<int>(v->row_segs.size()), static_cast<int>(v->col_segs.size()),
                          tol, lhs, rhs, scale, accept};
   CLEAVE_HIP(cleave::launch_verdict(va, stream));
@@ -942,6 +1033,31 @@ extern "C" int cleave_verify(cleave_plan* plan, const void* A, int64_t lda, int 
   if (plan && plan->batch > 0) return CLEAVE_EINVAL;   // batched plans use the batched / grouped calls
   return verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
                      accept, BatchLayout{}, hip_stream);
+}
+
+extern "C" int cleave_verify_reduce(cleave_plan* plan, const void* A, int64_t lda, int transA,
+                                    const void* B, int64_t ldb, int transB, int dtype,
+                                    const float* partials, const float* r, const float* s, double tol,
+                                    double* lhs, double* rhs, double* scale, int32_t* accept,
+                                    void* C, int64_t ldc, int out_dtype, void* hip_stream) {
+  if (!plan || plan->batch > 0 || !C) return CLEAVE_EINVAL;
+  if (out_dtype != CLEAVE_F32 && out_dtype != CLEAVE_BF16) return CLEAVE_EINVAL;
+  if (ldc < plan->N || !aligned(C, out_dtype == CLEAVE_BF16 ? 2 : 4)) return CLEAVE_EINVAL;
+  int rc = ensure_verify_tables_host(plan);
+  if (rc != CLEAVE_OK) return rc;
+  if (plan->verify->max_ksplit > static_cast<uint32_t>(cleave::kMaxFusedSplits)) {
+    // more splits per tile than the fused pass carries: the two passes one after the other
+    rc = verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
+                     accept, BatchLayout{}, hip_stream);
+    if (rc != CLEAVE_OK) return rc;
+    return reduce_impl(plan, partials, C, ldc, out_dtype, BatchLayout{}, hip_stream);
+  }
+  AggregateTarget agg;
+  agg.C = C;
+  agg.ldc = ldc;
+  agg.out_dtype = out_dtype;
+  return verify_impl(plan, A, lda, transA, B, ldb, transB, dtype, partials, r, s, tol, lhs, rhs, scale,
+                     accept, BatchLayout{}, hip_stream, agg);
 }
 
 extern "C" int cleave_verify_batched(cleave_plan* plan, const void* A, int64_t lda, int transA,

@@ -186,6 +186,32 @@ struct VerifyPassArgs {
 hipError_t launch_verify_pass(const VerifyPassArgs& args, int dtype, bool a_contig, bool b_contig,
                               bool vec, hipStream_t stream);
 
+// The same pass with the aggregation folded in: a run of rows of a tile is
+// taken for all of the tile's splits at once (the S blocks of a tile are
+// adjacent, each m_len * n_len elements), so that every partial element is
+// read once for both its check and the sum.  The runs are shorter than the
+// bilinear items of the separate pass (the pass also writes; short items
+// measured 15-25 % faster).  An item names the tile's first task; its sum for
+// split s goes to item_sums[item.slot + s * ipt], ipt = the task's slot count
+// (first_item[task + 1] - first_item[task]); C gets the left fold
+// ((P0 + P1) + ...) + P_{S-1} in fp32.  Splits per tile: at most kMaxFusedSplits.
+constexpr int kMaxFusedSplits = 8;
+struct AggregateArgs {
+  const VerifyItem* items;
+  int64_t n_items;
+  const uint32_t* first_item;     // per task: first slot; n_tasks + 1 entries
+  void* C;
+  int64_t ldc;                    // elements
+  int out_bf16;
+};
+struct VerifyReducePassArgs {
+  ProjectArgs A, B;
+  BilinearArgs bil;
+  AggregateArgs agg;
+};
+hipError_t launch_verify_reduce_pass(const VerifyReducePassArgs& args, int dtype, bool a_contig,
+                                     bool b_contig, bool vec, hipStream_t stream);
+
 // Per task: lhs = sum of its item sums (ascending), rhs = sum_k U[k] V[k] and
 // scale = sum_k |U|[k] |V|[k] over the task's chunk, accept = |lhs - rhs| <= tol * scale.
 struct VerdictArgs {

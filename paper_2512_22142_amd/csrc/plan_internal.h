@@ -113,7 +113,8 @@ struct Segment {
 // One unit of work of the bilinear-form kernel: a run of rows of one task's
 // partial block.
 struct VerifyItem {
-  uint32_t task, row0, rows, pad;
+  uint32_t task, row0, rows;
+  uint32_t slot;   // fused pass only: where the item's sum for the tile's first split goes
 };
 static_assert(sizeof(VerifyItem) == 16, "VerifyItem is 16 bytes");
 
@@ -122,6 +123,12 @@ struct VerifyTables {
   std::vector<uint32_t> task_row_seg, task_col_seg;   // per task
   std::vector<VerifyItem> items;                      // a task's items are adjacent
   std::vector<uint32_t> task_first_item;              // n_tasks + 1 entries
+  // Fused check + aggregation: its own, shorter items (runs of rows of a tile,
+  // taken for all splits at once; listed for the first split's task only) and
+  // the slots their sums go to (a task's slots are adjacent, as above).
+  std::vector<VerifyItem> agg_items;
+  std::vector<uint32_t> agg_first_item;               // n_tasks + 1 entries
+  uint32_t max_ksplit = 1;
   bool segs_mult8 = true;   // every segment start and length a multiple of 8
   bool segs_mult4 = true;
   // device copies and scratch (allocated once, on the device the plan lives on)
@@ -131,6 +138,9 @@ struct VerifyTables {
   uint32_t* d_task_col_seg = nullptr;
   VerifyItem* d_items = nullptr;
   uint32_t* d_task_first_item = nullptr;
+  VerifyItem* d_agg_items = nullptr;
+  uint32_t* d_agg_first_item = nullptr;
+  double* d_agg_item_sums = nullptr;
   double* d_proj = nullptr;       // U, |U| (row segs x K each), V, |V| (col segs x K each)
   double* d_item_sums = nullptr;  // one per item
 };

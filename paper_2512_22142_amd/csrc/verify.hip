@@ -8,6 +8,10 @@
 // vector fp64 rate is far above what the memory system feeds), each in a fixed
 // order, so the results are reproducible and exact for integer-valued inputs.
 //
+// The aggregation (Sec. 3.2) can ride along: the fused pass takes all splits
+// of a tile together and writes their sum while it checks them, so the
+// partial blocks are read once for both.
+//
 // Two launches:
 //   pass      three independent jobs in one grid --
 //             projections U[seg][k] = sum_i op(A)[i][k] r[i] over a row segment
@@ -31,6 +35,7 @@ constexpr int kThreads = 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ double bf16_bits_to_double(uint32_t bits16) {
   return static_cast<double>(__builtin_bit_cast(float, bits16 << 16));
@@ -318,6 +323,174 @@ __global__ __launch_bounds__(kThreads) void verify_pass_kernel(VerifyPassArgs a)
   }
 }
 
+// Round-to-nearest-even fp32 -> bf16 (NaN stays a quiet NaN).
+__device__ __forceinline__ uint32_t to_bf16_bits(float x) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// The bilinear items of all S splits of a tile over one run of rows, and the
+// tile's aggregated rows into C (paper Sec. 3.2 and Sec. 6: the PS checks the
+// returned blocks and aggregates them).  Per split the arithmetic and the
+// combination over lanes and waves are those of bilinear_item (over a shorter
+// run of rows); the fold over the splits is the aggregation kernel's,
+// ((P0 + P1) + P2) + ..., plain fp32 adds.
+template <bool VEC, int S>
+__device__ __forceinline__ void aggregate_item(const BilinearArgs& a, const AggregateArgs& g,
+                                               const VerifyItem& item, double* smem) {
+  const cleave_task task = a.tasks[item.task];            // the tile's first split
+  const uint32_t n_len = task.n_len;
+  const uint64_t block = static_cast<uint64_t>(task.m_len) * n_len;   // elements between two splits' blocks
+  const float* P = a.partials + task.partial_off + static_cast<uint64_t>(item.row0) * n_len;
+  const float* rr = a.r + task.m0 + item.row0;
+  const float* ss = a.s + task.n0;
+  const int64_t c_at = static_cast<int64_t>(task.m0 + item.row0) * g.ldc + task.n0;
+  const uint32_t count = item.rows * n_len;
+  double acc[S];
+#pragma unroll
+  for (int sp = 0; sp < S; ++sp) acc[sp] = 0.0;
+  if constexpr (VEC) {
+    constexpr uint32_t kStride = kThreads * 4;
+    constexpr int U = S <= 2 ? 8 : (S <= 4 ? 4 : 2);      // 16 loads of 16 bytes in flight per thread
+    const uint32_t q = kStride / n_len, rem = kStride - q * n_len;
+    uint32_t e = threadIdx.x * 4;
+    uint32_t row = e / n_len;
+    uint32_t col = e - row * n_len;
+    while (e < count) {
+      f32x4 p[U][S];
+      uint32_t rows[U], cols[U];
+      bool valid[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        valid[u] = e < count;
+#pragma unroll
+        for (int sp = 0; sp < S; ++sp)
+          p[u][sp] = valid[u] ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(P + sp * block + e))
+                              : f32x4{0.f, 0.f, 0.f, 0.f};
+        rows[u] = row;
+        cols[u] = col;
+        e += kStride;
+        row += q;
+        col += rem;
+        if (col >= n_len) {
+          col -= n_len;
+          ++row;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (valid[u]) {
+          const f32x4 s4 = *reinterpret_cast<const f32x4*>(ss + cols[u]);
+          const double rv = static_cast<double>(rr[rows[u]]);
+#pragma unroll
+          for (int sp = 0; sp < S; ++sp) {
+            double tsum = static_cast<double>(p[u][sp][0]) * static_cast<double>(s4[0]);
+            tsum = fma(static_cast<double>(p[u][sp][1]), static_cast<double>(s4[1]), tsum);
+            tsum = fma(static_cast<double>(p[u][sp][2]), static_cast<double>(s4[2]), tsum);
+            tsum = fma(static_cast<double>(p[u][sp][3]), static_cast<double>(s4[3]), tsum);
+            acc[sp] = fma(rv, tsum, acc[sp]);
+          }
+          f32x4 sum = p[u][0];
+#pragma unroll
+          for (int sp = 1; sp < S; ++sp) sum = sum + p[u][sp];
+          const int64_t off = c_at + static_cast<int64_t>(rows[u]) * g.ldc + cols[u];
+          if (g.out_bf16) {
+            u32x2 w;
+            w[0] = to_bf16_bits(sum[0]) | (to_bf16_bits(sum[1]) << 16);
+            w[1] = to_bf16_bits(sum[2]) | (to_bf16_bits(sum[3]) << 16);
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(g.C) + off) = w;
+          } else {
+            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + off) = sum;
+          }
+        }
+      }
+    }
+  } else {
+    for (uint32_t e = threadIdx.x; e < count; e += kThreads) {
+      const uint32_t row = e / n_len;
+      const uint32_t col = e - row * n_len;
+      const double rv = static_cast<double>(rr[row]);
+      const double sv = static_cast<double>(ss[col]);
+      float sum = 0.0f;
+#pragma unroll
+      for (int sp = 0; sp < S; ++sp) {
+        const float pv = P[sp * block + e];
+        acc[sp] = fma(rv, static_cast<double>(pv) * sv, acc[sp]);
+        sum = sp == 0 ? pv : sum + pv;
+      }
+      const int64_t off = c_at + static_cast<int64_t>(row) * g.ldc + col;
+      if (g.out_bf16) static_cast<uint16_t*>(g.C)[off] = static_cast<uint16_t>(to_bf16_bits(sum));
+      else static_cast<float*>(g.C)[off] = sum;
+    }
+  }
+#pragma unroll
+  for (int sp = 0; sp < S; ++sp) {
+    const double w = wave_sum(acc[sp]);
+    if ((threadIdx.x & 63) == 0) smem[sp * (kThreads / 64) + (threadIdx.x >> 6)] = w;
+  }
+  __syncthreads();
+  if (threadIdx.x < S) {
+    const uint32_t ipt = g.first_item[item.task + 1] - g.first_item[item.task];   // slots per task
+    double total = 0.0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) total += smem[threadIdx.x * (kThreads / 64) + w];
+    a.item_sums[item.slot + threadIdx.x * ipt] = total;
+  }
+  __syncthreads();   // smem is reused by the workgroup's next unit
+}
+
+template <bool VEC>
+__device__ __forceinline__ void aggregate_item_any(const BilinearArgs& a, const AggregateArgs& g, int64_t idx,
+                                                   double* smem) {
+  const VerifyItem it0 = g.items[idx];
+  switch (a.tasks[it0.task].ksplit_cnt) {               // uniform over the workgroup
+    case 1: aggregate_item<VEC, 1>(a, g, it0, smem); break;
+    case 2: aggregate_item<VEC, 2>(a, g, it0, smem); break;
+    case 3: aggregate_item<VEC, 3>(a, g, it0, smem); break;
+    case 4: aggregate_item<VEC, 4>(a, g, it0, smem); break;
+    case 5: aggregate_item<VEC, 5>(a, g, it0, smem); break;
+    case 6: aggregate_item<VEC, 6>(a, g, it0, smem); break;
+    case 7: aggregate_item<VEC, 7>(a, g, it0, smem); break;
+    default: aggregate_item<VEC, 8>(a, g, it0, smem); break;   // the caller admits at most kMaxFusedSplits
+  }
+}
+
+// The pass with the aggregation folded in: projection units and tile items in
+// one grid, spread as in verify_pass_kernel.
+template <int EB, bool VEC, bool A_CONTIG, bool B_CONTIG>
+__global__ __launch_bounds__(kThreads) void verify_reduce_pass_kernel(VerifyReducePassArgs a) {
+  constexpr int V = VEC ? 16 / EB : 1;
+  typedef typename pick<A_CONTIG, ProjectRows<EB, V>, ProjectStrided<EB, V>>::type ProjA;
+  typedef typename pick<B_CONTIG, ProjectRows<EB, V>, ProjectStrided<EB, V>>::type ProjB;
+  constexpr int kProjSmem = ProjA::kSmemDoubles > ProjB::kSmemDoubles ? ProjA::kSmemDoubles
+                                                                       : ProjB::kSmemDoubles;
+  constexpr int kAggSmem = kMaxFusedSplits * (kThreads / 64);
+  __shared__ double smem[kProjSmem > kAggSmem ? kProjSmem : kAggSmem];
+  const int64_t kbA = (a.A.K + ProjA::KW - 1) / ProjA::KW;
+  const int64_t kbB = (a.B.K + ProjB::KW - 1) / ProjB::KW;
+  const int64_t unitsA = kbA * a.A.n_segs * a.A.n_members;
+  const int64_t unitsB = kbB * a.B.n_segs * a.B.n_members;
+  const int64_t proj = unitsA + unitsB;
+  const int64_t total = proj + a.agg.n_items;
+  const int64_t every = proj > 0 ? total / proj : 1;
+  for (int64_t u = blockIdx.x; u < total; u += gridDim.x) {
+    const int64_t slot = u / every;
+    if (u % every == 0 && slot < proj) {
+      if (slot < unitsA) {
+        ProjA::run(a.A, static_cast<int>(slot / kbA), slot % kbA, smem);
+      } else {
+        const int64_t v = slot - unitsA;
+        ProjB::run(a.B, static_cast<int>(v / kbB), v % kbB, smem);
+      }
+    } else {
+      const int64_t before = (u + every - 1) / every;   // projection slots below u
+      aggregate_item_any<VEC>(a.bil, a.agg, u - (before < proj ? before : proj), smem);
+    }
+  }
+}
+
 // One workgroup per task; wave sums, then the four waves in order.
 __global__ __launch_bounds__(kThreads) void verdict_kernel(VerdictArgs a) {
   __shared__ double part[3][kThreads / 64];
@@ -394,6 +567,42 @@ hipError_t launch_verify_pass(const VerifyPassArgs& a, int dtype, bool a_contig,
   } else {
     if (vec) launch_pass_layouts<4, true>(a, a_contig, b_contig, grid, stream);
     else launch_pass_layouts<4, false>(a, a_contig, b_contig, grid, stream);
+  }
+  return hipGetLastError();
+}
+
+namespace {
+
+template <int EB, bool VEC>
+void launch_fused_layouts(const VerifyReducePassArgs& a, bool a_contig, bool b_contig, dim3 grid,
+                          hipStream_t stream) {
+  const dim3 block(kThreads);
+  if (a_contig && b_contig)
+    hipLaunchKernelGGL((verify_reduce_pass_kernel<EB, VEC, true, true>), grid, block, 0, stream, a);
+  else if (a_contig)
+    hipLaunchKernelGGL((verify_reduce_pass_kernel<EB, VEC, true, false>), grid, block, 0, stream, a);
+  else if (b_contig)
+    hipLaunchKernelGGL((verify_reduce_pass_kernel<EB, VEC, false, true>), grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL((verify_reduce_pass_kernel<EB, VEC, false, false>), grid, block, 0, stream, a);
+}
+
+}  // namespace
+
+hipError_t launch_verify_reduce_pass(const VerifyReducePassArgs& a, int dtype, bool a_contig, bool b_contig,
+                                     bool vec, hipStream_t stream) {
+  constexpr int kwRows = ProjectRows<2, 8>::KW, kwStrided = ProjectStrided<2, 8>::KW;
+  const int64_t kbA = (a.A.K + (a_contig ? kwRows : kwStrided / 2) - 1) / (a_contig ? kwRows : kwStrided / 2);
+  const int64_t kbB = (a.B.K + (b_contig ? kwRows : kwStrided / 2) - 1) / (b_contig ? kwRows : kwStrided / 2);
+  const int64_t units = kbA * a.A.n_segs * a.A.n_members + kbB * a.B.n_segs * a.B.n_members + a.agg.n_items;
+  if (units == 0) return hipSuccess;
+  const dim3 grid(static_cast<unsigned>(units < (int64_t{1} << 20) ? units : (int64_t{1} << 20)));
+  if (dtype == CLEAVE_BF16) {
+    if (vec) launch_fused_layouts<2, true>(a, a_contig, b_contig, grid, stream);
+    else launch_fused_layouts<2, false>(a, a_contig, b_contig, grid, stream);
+  } else {
+    if (vec) launch_fused_layouts<4, true>(a, a_contig, b_contig, grid, stream);
+    else launch_fused_layouts<4, false>(a, a_contig, b_contig, grid, stream);
   }
   return hipGetLastError();
 }
