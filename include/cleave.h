@@ -303,6 +303,21 @@ int cleave_reduce_adam_grouped(cleave_plan* plan, const float* partials, int64_t
                                float lr, float beta1, float beta2, float eps, float weight_decay,
                                int64_t step, void* hip_stream);
 
+/* Workgroup loads of the fast kernel's schedule (host only; for inspection
+ * and tests).  The fast bf16 kernel runs `grid` persistent workgroups over a
+ * list of work items (sub-tiles of tasks); when the items' chunk lengths
+ * differ -- heterogeneous tilings, Sec. 4.1 / Sec. 3.2 -- the library gives
+ * every workgroup a run of items of nearly equal total cost (longest items
+ * first, to the least-loaded workgroup, XCD-local where that costs nothing)
+ * instead of every grid-th item.  list: 0 = the 256 x 256 class, 1 = the
+ * 128 x 128 class, 2 = the all-small cut used when the large class has few
+ * items.  balanced = 0: loads[b] under the every-grid-th rule; 1: under the
+ * schedule the library uses (the same when all items are equal).  loads: host,
+ * grid doubles, in units of one 64-element K step (an item costs its steps
+ * plus 4.5 for its store phase).  CLEAVE_EINVAL: NULL, bad list, grid < 1. */
+int cleave_plan_schedule_loads(const cleave_plan* plan, int list, int grid, int balanced,
+                               double* loads);
+
 /* ---- verify --------------------------------------------------------------
  * Check of returned partial blocks by random projection (paper Sec. 6,
  * "Robustness to poisoning attacks": r^T (A B) s = (A^T r)^T (B s), matrix-

@@ -43,6 +43,7 @@ _BINDING_NAMES = (
     "reduce_batched",
     "reduce_grouped",
     "reduce_residual",
+    "schedule_loads",
     "verify",
     "verify_batched",
     "verify_reduce",

@@ -37,7 +37,7 @@ EXPORTS = (
     "cleave_plan_last_kernel", "cleave_verify", "cleave_plan_batched", "cleave_execute_batched",
     "cleave_reduce_batched", "cleave_reduce_residual", "cleave_reduce_adam",
     "cleave_shard_cost", "cleave_shard_fits", "cleave_assign", "cleave_reassign", "cleave_execute_assemble",
-    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped", "cleave_verify_batched", "cleave_verify_grouped", "cleave_verify_reduce",
+    "cleave_execute_grouped", "cleave_reduce_grouped", "cleave_execute_noalloc", "cleave_reassign_sets", "cleave_reduce_adam_grouped", "cleave_verify_batched", "cleave_verify_grouped", "cleave_verify_reduce", "cleave_plan_schedule_loads",
 )
 
 
@@ -126,6 +126,8 @@ def _load():
     lib.cleave_verify.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                   p, p, p, ctypes.c_double, p, p, p, p, p]
     lib.cleave_verify.restype = ctypes.c_int
+    lib.cleave_plan_schedule_loads.argtypes = [p, ctypes.c_int, ctypes.c_int, ctypes.c_int, p]
+    lib.cleave_plan_schedule_loads.restype = ctypes.c_int
     lib.cleave_verify_reduce.argtypes = [p, p, i64, ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int,
                                          p, p, p, ctypes.c_double, p, p, p, p, p, i64, ctypes.c_int, p]
     lib.cleave_verify_reduce.restype = ctypes.c_int
@@ -492,6 +494,16 @@ def _verify_vectors(plan, partials, r, s, accept, lhs, rhs, scale):
             vec(rhs, torch.float64, plan.num_tasks, "rhs", True),
             vec(scale, torch.float64, plan.num_tasks, "scale", True),
             vec(accept, torch.int32, plan.num_tasks, "accept"))
+
+
+def schedule_loads(plan, which, grid, balanced=True):
+    """cleave_plan_schedule_loads (host only): cost units per workgroup of the
+    fast kernel's schedule for list `which` (0 large class, 1 small class, 2
+    all-small cut) on `grid` workgroups."""
+    loads = np.zeros(int(grid), dtype=np.float64)
+    _check(_lib.cleave_plan_schedule_loads(plan._h, int(which), int(grid), int(bool(balanced)),
+                                           ctypes.c_void_p(loads.ctypes.data)), "cleave_plan_schedule_loads")
+    return loads
 
 
 def verify_reduce(plan, A, B, partials, r, s, tol, accept, C, lhs=None, rhs=None, scale=None,

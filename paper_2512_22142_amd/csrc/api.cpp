@@ -65,6 +65,11 @@ void free_device_tables(cleave_plan* p) {
   p->d_tasks = nullptr;
   if (p->d_items_fine) (void)hipFree(p->d_items_fine);
   p->d_items_fine = nullptr;
+  for (int list = 0; list < cleave::kNumTileClasses + 1; ++list) {
+    if (p->d_wg_ranges[list]) (void)hipFree(p->d_wg_ranges[list]);
+    p->d_wg_ranges[list] = nullptr;
+    p->wg_ranges_grid[list] = 0;
+  }
   p->d_items[0] = p->d_items[1] = nullptr;
   p->d_reduce_items = nullptr;
   p->device = -1;
@@ -147,9 +152,32 @@ int ensure_uploaded(cleave_plan* p) {
   int rc = ensure_device_ready(dev, nullptr);
   if (rc != CLEAVE_OK) return rc;
   rc = upload_vector(p->tasks, &p->d_tasks);
-  for (int c = 0; rc == CLEAVE_OK && c < cleave::kNumTileClasses; ++c)
-    rc = upload_vector(p->items[c], &p->d_items[c]);
-  if (rc == CLEAVE_OK) rc = upload_vector(p->items_fine, &p->d_items_fine);
+  // The three work-item lists; items of unequal length get a balanced workgroup
+  // schedule for this device's grid (a copy is reordered: the host lists keep
+  // their canonical order for the next device).
+  int cus = 0;
+  if (rc == CLEAVE_OK) rc = ensure_device_ready(dev, &cus);
+  for (int list = 0; rc == CLEAVE_OK && list < cleave::kNumTileClasses + 1; ++list) {
+    const bool fine = list == cleave::kNumTileClasses;
+    const int cls = fine ? cleave::kTileSmall : list;
+    const std::vector<cleave::WorkItem>& host = fine ? p->items_fine : p->items[list];
+    const size_t n_direct = fine ? p->items_fine_whole_steps : p->items_whole_steps[list];
+    cleave::WorkItem** dst = fine ? &p->d_items_fine : &p->d_items[list];
+    const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(cls);
+    const int grid = static_cast<int>(std::min<int64_t>(static_cast<int64_t>(n_direct), resident));
+    std::vector<uint32_t> ranges;
+    try {
+      std::vector<cleave::WorkItem> copy(host);
+      cleave::balance_work_items(copy, n_direct, grid, &ranges);
+      rc = upload_vector(ranges.empty() ? host : copy, dst);
+    } catch (const std::bad_alloc&) {
+      rc = CLEAVE_ENOMEM;
+    }
+    if (rc == CLEAVE_OK && !ranges.empty()) {
+      rc = upload_vector(ranges, &p->d_wg_ranges[list]);
+      p->wg_ranges_grid[list] = grid;
+    }
+  }
   if (rc == CLEAVE_OK) rc = upload_vector(p->reduce_items, &p->d_reduce_items);
   if (rc == CLEAVE_OK) rc = allocate_subset_ring(p);
   if (rc != CLEAVE_OK) {
@@ -434,7 +462,10 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
   // leading items of each list whose chunk is a whole number of direct-kernel K steps
   int64_t whole_steps[cleave::kNumTileClasses] = {static_cast<int64_t>(plan->items_whole_steps[0]),
                                                   static_cast<int64_t>(plan->items_whole_steps[1])};
+  // which of the plan's lists a class runs from (-1: a subset's own list)
+  int list_of[cleave::kNumTileClasses] = {task_ids ? -1 : 0, task_ids ? -1 : 1};
   if (!task_ids && prefers_fine(plan->items[cleave::kTileLarge].size())) {
+    list_of[cleave::kTileSmall] = cleave::kNumTileClasses;
     d_lists[cleave::kTileLarge] = nullptr;
     counts[cleave::kTileLarge] = 0;
     whole_steps[cleave::kTileLarge] = 0;
@@ -522,7 +553,11 @@ int execute_impl(cleave_plan* plan, const int64_t* task_ids, int64_t n_ids, cons
       args.n_items = n_direct;
       const int64_t resident = static_cast<int64_t>(cus) * cleave::direct_workgroups_per_cu(c);
       const int grid = static_cast<int>(std::min<int64_t>(n_direct, resident));
+      // items of unequal length: the schedule made for this grid when the tables were uploaded
+      const int list = list_of[c];
+      args.wg_ranges = (list >= 0 && plan->wg_ranges_grid[list] == grid) ? plan->d_wg_ranges[list] : nullptr;
       const hipError_t he = cleave::launch_execute_direct(args, c, grid, stream);
+      args.wg_ranges = nullptr;
       if (he != hipSuccess) return launch_failed(he);
     }
     if (n_staged > 0) {

@@ -267,7 +267,8 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
       if (st < c.steps) issue(c, st, st);
   };
 
-  // Work items are walked with the grid as stride.  The ring runs on across
+  // A workgroup walks its work items -- every grid-th one, or a run of its own
+  // when the launch comes with a balanced schedule.  The ring runs on across
   // items: when the current item and the next one are both full sub-tiles, the
   // next item's first two K steps are fetched into the ring stages that this
   // item's last two steps free, exactly as this item's own later steps would
@@ -286,17 +287,23 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
   static_assert(MB % 2 == 0, "the epilogue stores a sub-tile in two halves of block rows");
   unsigned char* const image = smem + STAGES * kStage + wave * kBlockImageBytes;
 
-  const int64_t stride = gridDim.x;
-  if (static_cast<int64_t>(blockIdx.x) >= args.n_items) return;
-  ItemCtx c = make_ctx(load_item(blockIdx.x));
+  // This workgroup's items: first, first + stride, ... below it_end.
+  int64_t it_first = blockIdx.x, it_end = args.n_items, stride = gridDim.x;
+  if (args.wg_ranges) {
+    it_first = args.wg_ranges[blockIdx.x];
+    it_end = args.wg_ranges[blockIdx.x + 1];
+    stride = 1;
+  }
+  if (it_first >= it_end) return;
+  ItemCtx c = make_ctx(load_item(it_first));
   fill_ring(c);
-  int64_t it_next = static_cast<int64_t>(blockIdx.x) + stride;
+  int64_t it_next = it_first + stride;
   // Item records are read two items ahead (scalar loads through the constant
   // address space): the read for the item after next is issued right behind
   // the current item's first barrier, a whole K step before the next wait
   // that covers it.  `last_item` stands in for records past the end.
-  const int64_t last_item = args.n_items - 1;
-  ItemCtx nx = make_ctx(load_item(it_next < args.n_items ? it_next : last_item));
+  const int64_t last_item = it_end - 1;
+  ItemCtx nx = make_ctx(load_item(it_next < it_end ? it_next : last_item));
   WorkItem after_next;
   // How the current item's first two steps got into the ring.
   //   kFilled:             ring filled from empty, nothing issued since.
@@ -380,7 +387,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
 
   for (;;) {
     const int steps = c.steps;
-    const bool has_next = it_next < args.n_items;
+    const bool has_next = it_next < it_end;
     const bool interior = c.m_valid == TM && c.n_valid == TN;
     const bool wide = interior && args.out_vec;   // stores of whole lines through the block image
     // hand the ring over without draining it
@@ -449,7 +456,7 @@ __global__ __launch_bounds__(S::NT, S::WGS) void execute_direct_kernel(ExecuteAr
         } else if (cont && s + STAGES - steps < nx.steps) {
           issue(nx, s + STAGES - steps, st);
         }
-        if (s == 0) after_next = load_item(it_next + stride < args.n_items ? it_next + stride : last_item);
+        if (s == 0) after_next = load_item(it_next + stride < it_end ? it_next + stride : last_item);
         if (!last || cont) read_frags(oth, int_c<0>{}, 0);
       }
       mma((kSub - 1) & 1, std::false_type{});

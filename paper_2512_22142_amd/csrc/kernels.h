@@ -53,6 +53,9 @@ struct ExecuteArgs {
   // The output (partials, or C in assemble mode) takes a 16-byte (fp32) or
   // 8-byte (bf16) store at every fourth column of every sub-tile row.
   int out_vec;
+  // Direct kernel only.  Null: workgroup b takes items b, b + grid, ...
+  // Otherwise grid + 1 entries: workgroup b takes items [wg_ranges[b], wg_ranges[b + 1]).
+  const uint32_t* wg_ranges;
 };
 
 // Enqueues the execute kernel for one tile class.  `vec` selects the 16-byte

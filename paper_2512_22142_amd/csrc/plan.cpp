@@ -248,6 +248,45 @@ int finish_plan(int64_t M, int64_t N, int64_t K, const std::vector<Tile>& tiles,
 
 }  // namespace
 
+void balance_work_items(std::vector<WorkItem>& items, size_t n_direct, int grid,
+                        std::vector<uint32_t>* ranges) {
+  ranges->clear();
+  if (grid < 2 || n_direct <= static_cast<size_t>(grid)) return;   // one item per workgroup at most
+  const auto cost = [&](size_t i) { return work_item_cost(items[i]); };
+  bool equal = true;
+  for (size_t i = 1; i < n_direct && equal; ++i) equal = items[i].k_len == items[0].k_len;
+  if (equal) return;
+
+  std::vector<uint32_t> by_cost(n_direct);
+  for (size_t i = 0; i < n_direct; ++i) by_cost[i] = static_cast<uint32_t>(i);
+  std::stable_sort(by_cost.begin(), by_cost.end(),
+                   [&](uint32_t a, uint32_t b) { return items[a].k_len > items[b].k_len; });
+  std::vector<double> load(static_cast<size_t>(grid), 0.0);
+  std::vector<std::vector<uint32_t>> owned(static_cast<size_t>(grid));
+  for (uint32_t i : by_cost) {
+    const int home = static_cast<int>(i % kXcds);
+    int best_home = -1, best_any = 0;
+    for (int b = 0; b < grid; ++b) {
+      if (load[b] < load[best_any]) best_any = b;
+      if (b % kXcds == home && (best_home < 0 || load[b] < load[best_home])) best_home = b;
+    }
+    const double c = cost(i);
+    const int b = (best_home >= 0 && load[best_home] <= load[best_any] + c) ? best_home : best_any;
+    load[b] += c;
+    owned[b].push_back(i);
+  }
+  std::vector<WorkItem> out;
+  out.reserve(n_direct);
+  ranges->reserve(static_cast<size_t>(grid) + 1);
+  for (int b = 0; b < grid; ++b) {
+    ranges->push_back(static_cast<uint32_t>(out.size()));
+    std::sort(owned[b].begin(), owned[b].end());
+    for (uint32_t i : owned[b]) out.push_back(items[i]);
+  }
+  ranges->push_back(static_cast<uint32_t>(out.size()));
+  std::copy(out.begin(), out.end(), items.begin());
+}
+
 void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out,
                        bool fine) {
   const SubTiling s = sub_tiling(t, fine);
@@ -367,3 +406,25 @@ extern "C" const char* cleave_strerror(int status) {
   }
 }
 
+extern "C" int cleave_plan_schedule_loads(const cleave_plan* plan, int list, int grid, int balanced,
+                                          double* loads) {
+  if (!plan || !loads || list < 0 || list > cleave::kNumTileClasses || grid < 1) return CLEAVE_EINVAL;
+  const bool fine = list == cleave::kNumTileClasses;
+  const std::vector<cleave::WorkItem>& host = fine ? plan->items_fine : plan->items[list];
+  const size_t n_direct = fine ? plan->items_fine_whole_steps : plan->items_whole_steps[list];
+  std::fill(loads, loads + grid, 0.0);
+  try {
+    std::vector<cleave::WorkItem> items(host.begin(), host.begin() + static_cast<std::ptrdiff_t>(n_direct));
+    std::vector<uint32_t> ranges;
+    if (balanced) cleave::balance_work_items(items, n_direct, grid, &ranges);
+    if (!ranges.empty()) {
+      for (int b = 0; b < grid; ++b)
+        for (uint32_t i = ranges[b]; i < ranges[b + 1]; ++i) loads[b] += cleave::work_item_cost(items[i]);
+    } else {
+      for (size_t i = 0; i < n_direct; ++i) loads[i % static_cast<size_t>(grid)] += cleave::work_item_cost(items[i]);
+    }
+  } catch (const std::bad_alloc&) {
+    return CLEAVE_ENOMEM;
+  }
+  return CLEAVE_OK;
+}

@@ -175,6 +175,27 @@ struct SubsetRing {
 // `fine` every block is cut into small-class sub-tiles.  Either cut gives the
 // same bits: both kernels shapes accumulate an output element in the same
 // order (ascending K steps and sub-steps), so the choice is free per launch.
+// Workgroup schedule for a list of work items of unequal length (heterogeneous
+// tilings: Sec. 4.1 gives every device its own shard size, Sec. 3.2 its own
+// split of the inner dimension).  The persistent kernel's default -- workgroup
+// b takes items b, b + grid, ... -- leaves the workgroups with very different
+// totals when chunk lengths differ by a factor of eight.  This reorders the
+// first n_direct items so that workgroup b owns the contiguous run
+// [ranges[b], ranges[b + 1]) and the runs have nearly equal cost: longest items
+// first, each to the least-loaded workgroup of the XCD the item's position
+// belongs to (position mod 8, as the list was laid out) unless a workgroup of
+// another XCD is behind by more than the item's own cost; inside a run the
+// original order is kept.  Returns with `ranges` empty, and the list
+// untouched, when all items cost the same or no workgroup gets a second item.
+void balance_work_items(std::vector<WorkItem>& items, size_t n_direct, int grid,
+                        std::vector<uint32_t>* ranges);
+// Cost of a work item in the schedule's unit (one K step of the fast kernel):
+// its K steps plus a constant for the store phase (measured: 12 K clocks
+// against 2.6 K per step).
+inline double work_item_cost(const WorkItem& w) {
+  return w.k_len / kDirectKStep + 4.5;
+}
+
 void append_work_items(const cleave_task& t, uint32_t task_index, std::vector<WorkItem>* out,
                        bool fine = false);
 
@@ -207,6 +228,10 @@ struct cleave_plan {
   cleave_task* d_tasks = nullptr;
   cleave::WorkItem* d_items[cleave::kNumTileClasses] = {nullptr, nullptr};
   cleave::WorkItem* d_items_fine = nullptr;
+  // Balanced schedules of the three lists' direct parts (large, small, fine) for
+  // the grid sizes of the device the tables were uploaded to; null = equal items.
+  uint32_t* d_wg_ranges[cleave::kNumTileClasses + 1] = {nullptr, nullptr, nullptr};
+  int wg_ranges_grid[cleave::kNumTileClasses + 1] = {0, 0, 0};
   cleave::ReduceItem* d_reduce_items = nullptr;
   // Work-item slices of subset launches (device memory sized once, at upload).
   cleave::SubsetRing subset;

@@ -123,3 +123,53 @@ def test_execute_and_reduce_replay_from_a_hip_graph():
         # eager work of the program between replays
         cleave.execute(plan, A, B, parts)
         torch.cuda.synchronize()
+
+
+def test_both_tile_classes_and_unequal_items_on_a_caller_stream_and_from_a_hip_graph():
+    """A tiling with 512-wide and 128-wide tiles and 1, 2 or 4 splits: a full
+    execute call launches both tile classes, each with a balanced workgroup
+    schedule.  The reduce enqueued right behind it reads finished blocks --
+    on the default stream, on a caller stream, and replayed from a graph."""
+    M, N, K = 2560, 2304, 1024
+    band_h = [512, 128, 512, 128, 512, 128, 512, 128]
+    col_w = [[512, 128, 512, 128, 512, 512] for _ in band_h]
+    ks = [(1, 2, 4)[(i + j) % 3] for i in range(len(band_h)) for j in range(6)]
+    plan = cleave.plan_explicit(M, N, K, band_h, col_w, ks)
+    tasks, elems = planner.plan_explicit(M, N, K, band_h, col_w, ks)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    A_cpu = make_matrix(221, M, K, "bf16", integer_valued=True)
+    B_cpu = make_matrix(222, K, N, "bf16", integer_valued=True)
+    A, B = A_cpu.cuda(), B_cpu.cuda()
+    opA, opB = og.logical_operands(A_cpu, 0, B_cpu, 0)
+    ref = og.gemm(opA, opB)
+    parts = torch.full((elems,), float("nan"), dtype=torch.float32, device="cuda")
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    cleave.execute(plan, A, B, parts)
+    cleave.reduce(plan, parts, C)
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), ref)
+    # a caller stream of its own
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        parts.fill_(float("nan"))
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        cleave.execute(plan, A, B, parts, stream=side)
+        cleave.reduce(plan, parts, C, stream=side)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy().astype(np.float64), ref)
+    # captured once, replayed
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cleave.execute(plan, A, B, parts)
+        cleave.reduce(plan, parts, C)
+    for replay in range(3):
+        parts.fill_(float("nan"))
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy().astype(np.float64), ref), replay
+        cleave.execute(plan, A, B, parts)      # eager work of the program between replays
+        torch.cuda.synchronize()

@@ -110,3 +110,40 @@ def test_outputs_that_only_take_element_stores_exact(out):
         assert np.array_equal(got, want)
         pad = torch.cat([wide[:, :1], wide[:, N + 1:]], dim=1).float().cpu().numpy()
         assert np.isnan(pad).all()          # nothing written outside the view
+
+
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0)])
+def test_items_of_unequal_length_take_the_balanced_schedule_exact(transA, transB):
+    """Tiles with 1, 2, 4 and 8 splits of the inner dimension in one plan: chunk
+    lengths differ by a factor of eight, so the library gives every workgroup a
+    run of items of its own (longest items placed first) instead of every
+    grid-th item.  Several items per workgroup; every block and C exact."""
+    M, N, K = 4096, 6144, 512
+    band_h = [512] * 8
+    col_w = [[512] * 12 for _ in band_h]
+    ks = [(1, 2, 4, 8)[(3 * i + j) % 4] for i in range(8) for j in range(12)]
+    plan = cleave.plan_explicit(M, N, K, band_h, col_w, ks)
+    tasks, _ = planner.plan_explicit(M, N, K, band_h, col_w, ks)
+    assert plan.tasks.tobytes() == tasks.tobytes()
+    # every task is a 512 x 512 block: four 256 x 256 work items
+    assert 4 * len(tasks) > 2 * _resident_workgroups(1)
+    a = make_matrix(801, M, K, "bf16", integer_valued=True)
+    b = make_matrix(802, K, N, "bf16", integer_valued=True)
+    run = GpuGemm(plan, stored(a, transA), stored(b, transB), transA, transB).run()
+    assert "direct" in plan.last_kernel
+    parts, C = run.partials_host(), run.C_host()
+    opA, opB = og.logical_operands(stored(a, transA), transA, stored(b, transB), transB)
+    bounds = sorted(set((int(t["k0"]), int(t["k0"]) + int(t["k_len"])) for t in tasks))
+    ref_of = {kb: og.gemm(opA, opB, kb[0], kb[1]) for kb in bounds}
+    for t in tasks:
+        m0, ml, n0, nl = int(t["m0"]), int(t["m_len"]), int(t["n0"]), int(t["n_len"])
+        ref = ref_of[(int(t["k0"]), int(t["k0"]) + int(t["k_len"]))]
+        assert np.array_equal(block_of(parts, t), ref[m0:m0 + ml, n0:n0 + nl]), (int(t["tile_id"]), int(t["ksplit_idx"]))
+    assert np.array_equal(C, og.gemm(opA, opB))
+    # a re-issued subset goes the unbalanced way (its list is made on the device): same bits
+    ids = [int(i) for i in range(0, len(tasks), 7)]
+    run.partials[:] = float("nan")
+    run.execute(task_ids=ids)
+    again = run.partials_host()
+    for i in ids:
+        assert np.array_equal(block_of(again, tasks[i]), block_of(parts, tasks[i]))

@@ -141,3 +141,48 @@ def test_batched_plan_rejects_empty_batch_and_bad_split():
         with pytest.raises(cleave.CleaveError) as e:
             cleave.plan_batched(*args)
         assert e.value.status == -1
+
+
+# ---- workgroup schedule of the fast kernel (host logic) -----------------------
+
+def _loads(plan, which, grid):
+    import paper_2512_22142_amd as cleave
+    return cleave.schedule_loads(plan, which, grid, False), cleave.schedule_loads(plan, which, grid, True)
+
+
+def test_schedule_of_equal_items_is_the_strided_one():
+    import paper_2512_22142_amd as cleave
+    plan = cleave.plan_uniform(4096, 4096, 4096, 512, 512, 4)      # 1024 items of 16 K steps
+    strided, used = _loads(plan, 0, 256)
+    assert np.array_equal(strided, used)
+    assert np.all(used == 4 * (16 + 4.5))
+
+
+def test_schedule_of_unequal_items_is_balanced():
+    """Tiles with 1, 2, 4, 8 splits: the schedule conserves the work, beats the
+    every-grid-th rule, and meets the bound of longest-first list scheduling
+    (no workgroup exceeds the mean by more than one item -- the longest)."""
+    import paper_2512_22142_amd as cleave
+    M, N, K = 4096, 6144, 4096
+    band_h = [512] * 8
+    col_w = [[512] * 12 for _ in band_h]
+    ks = [(1, 2, 4, 8)[(3 * i + j) % 4] for i in range(8) for j in range(12)]
+    plan = cleave.plan_explicit(M, N, K, band_h, col_w, ks)
+    for grid in (256, 304, 64):
+        strided, used = _loads(plan, 0, grid)
+        assert abs(strided.sum() - used.sum()) < 1e-9 and used.min() > 0
+        longest = K / 64 + 4.5
+        assert used.max() <= used.mean() + longest + 1e-9
+        assert used.max() < strided.max()
+        assert used.mean() / used.max() > 0.9, (grid, used.mean() / used.max())
+    # fewer items than workgroups: one item each, nothing to balance
+    strided, used = _loads(plan, 0, 4096)
+    assert np.array_equal(strided, used)
+
+
+def test_schedule_loads_argument_errors():
+    import paper_2512_22142_amd as cleave
+    plan = cleave.plan_uniform(512, 512, 512, 256, 256, 1)
+    for which, grid in ((3, 8), (-1, 8), (0, 0)):
+        with pytest.raises(cleave.CleaveError):
+            cleave.schedule_loads(plan, which, grid)
