@@ -35,8 +35,8 @@ PEAK_HBM_GBPS = 8000.0
 # dropped on a mismatch.
 COUNTER_TRAFFIC = {
     "workload": "c3",
-    "sources_sha256": "262c43bd6cd45ec8b9923951a70caa37337d7cbe5a4f2777b080591c082bfa3b",
-    "execute_bytes_per_launch": (2.0 * 225733 + 388535) * 1024,
+    "sources_sha256": "ff8180cab31c4ab161b80555ce39918b330bb492191138eb9821767c49c354ab",
+    "execute_bytes_per_launch": (2.0 * 225612 + 388535) * 1024,
     "reduce_bytes_per_launch": (2.0 * 194743 + 97134) * 1024,
 }
 
